@@ -1,0 +1,127 @@
+/*
+ * libmoda -- Mixture-of-Depths Attention (MoDA) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every data pointer is a DEVICE pointer owned by the caller; the
+ * shape struct and the return values live on the host.  The library never
+ * allocates, frees or keeps a pointer; its only scratch is the workspace the
+ * caller passes to the backward call.  Calls are asynchronous on the given HIP
+ * stream (NULL = the default stream), never synchronise the device, and hold
+ * no global mutable state.  Errors are reported by return code only: on any
+ * status other than MODA_OK no kernel has been launched and no output has
+ * been touched.
+ *
+ * The operator (paper section 2.2 "Mixture-of-Depths Attention"; Eq. 2 for the
+ * sequence part; Algorithm 1 for the index sets and the shared online-softmax
+ * state): for batch b, query head h (kv head g = h / (Hq/Hk)) and position t,
+ * ONE softmax runs over
+ *   - the sequence keys  Kseq[b,g,j],  j <= t  (all j < T when causal == 0;
+ *     the diagonal j == t is visible), and
+ *   - the depth keys     Kdepth[b,g,t,i],  i < depth_count: the keys that
+ *     preceding layers produced at the query's own position t,
+ * with logits scale * <Q[b,h,t], key>.  O[b,h,t] is the weighted sum of the
+ * matching values (Vseq[b,g,j], Vdepth[b,g,t,i]) under that one normaliser
+ * (Algorithm 1's final o / acc), and LSE[b,h,t] = max logit + ln(sum of
+ * exp(logit - max)) in natural-log units.  depth_count == 0 is plain
+ * (causal) attention.
+ *
+ * Layouts: contiguous row-major, base pointers 16-byte aligned.
+ *   Q, O, dO, dQ                  [B, Hq, T, d]
+ *   Kseq, Vseq, dKseq, dVseq      [B, Hk, T, d]
+ *   Kdepth, Vdepth, dKdepth, ...  [B, Hk, T, depth_alloc, d]
+ *                                 (position-major: the depth_alloc slots of one
+ *                                 position are adjacent -- the paper's
+ *                                 "flash-compatible depth KV layout" with the
+ *                                 flattened T*L axis kept as two indices)
+ *   LSE                           [B, Hq, T], always fp32
+ * Element type of everything but LSE is `dtype`.  Outputs must not alias
+ * inputs.  Kdepth/Vdepth (and their gradients) may be NULL iff
+ * depth_count == 0.
+ */
+#ifndef MODA_H_
+#define MODA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MODA_OK = 0,
+  MODA_ERR_NULL = 1,        /* a required pointer is NULL                        */
+  MODA_ERR_SHAPE = 2,       /* a dimension is negative / inconsistent            */
+  MODA_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for        */
+  MODA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned             */
+  MODA_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch                */
+  MODA_ERR_WORKSPACE = 6    /* workspace is NULL or smaller than required        */
+} moda_status;
+
+typedef enum { MODA_F32 = 0, MODA_BF16 = 1 } moda_dtype;
+
+typedef struct {
+  int32_t B;           /* batch, >= 0 (0 is a valid empty call)                           */
+  int32_t Hq;          /* query heads, > 0                                                */
+  int32_t Hk;          /* key/value heads, > 0, Hq % Hk == 0                              */
+  int32_t T;           /* sequence length, T_q == T_kv == T, >= 0                         */
+  int32_t d;           /* head dimension: 64 or 128                                       */
+  int32_t depth_alloc; /* slots allocated per position in Kdepth/Vdepth (the stride)      */
+  int32_t depth_count; /* slots [0, depth_count) are attended; <= depth_alloc             */
+  int32_t causal;      /* 1: sequence keys j <= t (Eq. 2's causal mask); 0: all T keys    */
+  float scale;         /* softmax scale; <= 0 selects Eq. 2's 1/sqrt(d)                   */
+  int32_t dtype;       /* a moda_dtype: type of Q, K, V, depth tensors, O, dO, gradients  */
+} moda_shape;
+
+/*
+ * Forward pass of the operator defined above (Algorithm 1: sequence blocks,
+ * then the depth slots, folded into one running max / normaliser / output,
+ * one final division).
+ *   in : Q, Kseq, Vseq, Kdepth, Vdepth   device, read-only
+ *   out: O (dtype), LSE (fp32)           device, fully overwritten
+ * Returns MODA_OK after enqueueing the work on `hip_stream` (a hipStream_t
+ * passed as void*).  B == 0 or T == 0 returns MODA_OK without launching.
+ */
+moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                          const void* Vdepth, void* O, float* LSE, const moda_shape* s,
+                          void* hip_stream);
+
+/*
+ * Backward pass.  The paper times it (Table 2, "forward&backward") but gives
+ * no algorithm; it is the derivative of the forward definition: with softmax
+ * weights p over the union, g = dO[b,h,t] and delta = <g, O[b,h,t]>,
+ *   dV_c += p_c g;  e_c = p_c (<g, v_c> - delta);
+ *   dQ[b,h,t] = scale * sum_c e_c k_c;  dK_c += scale * e_c Q[b,h,t],
+ * where a sequence key sums over every query that sees it (and the Hq/Hk query
+ * heads of its kv head) and a depth slot (t,i) only over the queries at t.
+ *   in : Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE (from moda_attn_fwd), dO
+ *   out: dQ, dKseq, dVseq, dKdepth, dVdepth (dtype), fully overwritten; depth
+ *        gradient slots >= depth_count are written as zero
+ *   workspace: device scratch of at least moda_attn_bwd_workspace_bytes(s)
+ *        bytes, 16-byte aligned; contents on entry are ignored.
+ */
+size_t moda_attn_bwd_workspace_bytes(const moda_shape* s);
+moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                          const void* Vdepth, const void* O, const float* LSE, const void* dO,
+                          void* dQ, void* dKseq, void* dVseq, void* dKdepth, void* dVdepth,
+                          void* workspace, size_t workspace_bytes, const moda_shape* s,
+                          void* hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* moda_status_string(moda_status st);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int moda_version(void);
+
+/*
+ * Time of the most recent forward (which = 0) or backward (which = 1) launch
+ * sequence of this thread is NOT tracked by the library; callers time with HIP
+ * events on their own stream.  This helper only reports how many kernels one
+ * call of the given kind launches for shape `s` (0 for an empty problem), so a
+ * profiler's per-kernel rows can be matched to calls.
+ */
+int moda_kernels_per_call(const moda_shape* s, int which);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MODA_H_ */

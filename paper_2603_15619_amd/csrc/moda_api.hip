@@ -1,0 +1,96 @@
+// libmoda C ABI: argument validation and kernel dispatch (host code only).
+#include <math.h>
+
+#include "../../include/moda.h"
+#include "moda_launch.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape checks shared by forward and backward.  Returns MODA_OK if the shape is
+// one this build can run.
+moda_status check_shape(const moda_shape* s) {
+  if (!s) return MODA_ERR_NULL;
+  if (s->B < 0 || s->T < 0 || s->Hq <= 0 || s->Hk <= 0 || s->d <= 0) return MODA_ERR_SHAPE;
+  if (s->Hq % s->Hk != 0) return MODA_ERR_SHAPE;
+  if (s->depth_count < 0 || s->depth_alloc < s->depth_count) return MODA_ERR_SHAPE;
+  if (s->causal != 0 && s->causal != 1) return MODA_ERR_SHAPE;
+  if (s->dtype != MODA_F32 && s->dtype != MODA_BF16) return MODA_ERR_UNSUPPORTED;
+  if (s->d != 64 && s->d != 128) return MODA_ERR_UNSUPPORTED;
+  if (!(s->scale == s->scale) || isinf(s->scale)) return MODA_ERR_SHAPE;  // NaN / inf
+  return MODA_OK;
+}
+
+float resolve_scale(const moda_shape* s) {
+  return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moda_status_string(moda_status st) {
+  switch (st) {
+    case MODA_OK: return "ok";
+    case MODA_ERR_NULL: return "a required pointer is NULL";
+    case MODA_ERR_SHAPE: return "invalid or inconsistent shape";
+    case MODA_ERR_UNSUPPORTED: return "unsupported dtype or head dimension";
+    case MODA_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case MODA_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+    case MODA_ERR_WORKSPACE: return "workspace missing or too small";
+  }
+  return "unknown status";
+}
+
+int moda_version(void) { return 100; }
+
+int moda_kernels_per_call(const moda_shape* s, int which) {
+  if (check_shape(s) != MODA_OK || s->B == 0 || s->T == 0) return 0;
+  if (which == 0) return 1;
+  return 0;
+}
+
+moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                          const void* Vdepth, void* O, float* LSE, const moda_shape* s,
+                          void* hip_stream) {
+  moda_status st = check_shape(s);
+  if (st != MODA_OK) return st;
+  if (s->B == 0 || s->T == 0) return MODA_OK;
+  if (!Q || !Kseq || !Vseq || !O || !LSE) return MODA_ERR_NULL;
+  if (s->depth_count > 0 && (!Kdepth || !Vdepth)) return MODA_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(Kseq) || !aligned16(Vseq) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(Kdepth) || !aligned16(Vdepth))
+    return MODA_ERR_ALIGN;
+
+  moda::FwdParams p;
+  p.Q = Q; p.Kseq = Kseq; p.Vseq = Vseq; p.Kdepth = Kdepth; p.Vdepth = Vdepth;
+  p.O = O; p.LSE = LSE;
+  p.B = s->B; p.Hq = s->Hq; p.Hk = s->Hk; p.T = s->T;
+  p.depth_alloc = s->depth_alloc; p.depth_count = s->depth_count;
+  p.causal = s->causal;
+  p.scale = resolve_scale(s);
+  p.scale_log2 = p.scale * 1.4426950408889634f;
+  const int rows = moda::fwd_bf16_tile_rows();
+  p.n_qtiles = (s->T + rows - 1) / rows;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (s->dtype == MODA_BF16) ? moda::launch_fwd_bf16(p, s->d, stream)
+                                         : moda::launch_fwd_f32(p, s->d, stream);
+  return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
+}
+
+size_t moda_attn_bwd_workspace_bytes(const moda_shape* s) {
+  (void)s;
+  return 0;
+}
+
+moda_status moda_attn_bwd(const void*, const void*, const void*, const void*, const void*,
+                          const void*, const float*, const void*, void*, void*, void*, void*,
+                          void*, void*, size_t, const moda_shape* s, void*) {
+  moda_status st = check_shape(s);
+  if (st != MODA_OK) return st;
+  return MODA_ERR_UNSUPPORTED;  // backward kernels are not built yet
+}
+
+}  // extern "C"

@@ -1,0 +1,12 @@
+// Host-side launchers, one per kernel family; implemented next to the kernels.
+#pragma once
+#include "moda_common.h"
+
+namespace moda {
+
+// Rows of queries handled by one workgroup of the bf16 forward kernel.
+int fwd_bf16_tile_rows();
+hipError_t launch_fwd_bf16(const FwdParams& p, int d, hipStream_t stream);
+hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream);
+
+}  // namespace moda
