@@ -25,6 +25,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kQPerWave = 64;
 constexpr int kBM = kWaves * kQPerWave;  // 256 queries per workgroup
 constexpr int kBN = 64;                  // keys per LDS tile
+constexpr int kDepthChunk = 16;          // depth slots whose loads are in flight together
 
 template <int D>
 struct FwdCfg {
@@ -293,65 +294,62 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     for (int it = 0; it < 32 / RPS; ++it) {
       const int row = it * RPS + rg;
       const int t = qw0 + nb * 32 + row;
-      if (t < T) {
-        f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
-        f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
-        float o[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
-        float m = ml[2 * row];
-        float l = ml[2 * row + 1];
-        if (L > 0) {
-          u32x4 qv = *(const u32x4*)(Qb + (size_t)t * C::kRowBytes + l16 * 16);
-          const char* kd = Kdb + (size_t)t * drow + l16 * 16;
-          const char* vd = Vdb + (size_t)t * drow + l16 * 16;
-          for (int i0 = 0; i0 < L; i0 += 16) {
-            float sc[16];
-            float mx = m;
+      const int tc = min(t, T - 1);  // rows past the end compute on row T-1 and are not stored
+      f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
+      f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
+      float o[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
+      float m = ml[2 * row];
+      float l = ml[2 * row + 1];
+      if (L > 0) {
+        const u32x4 qv = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
+        const char* kd = Kdb + (size_t)tc * drow + l16 * 16;
+        const char* vd = Vdb + (size_t)tc * drow + l16 * 16;
+        for (int i0 = 0; i0 < L; i0 += kDepthChunk) {
+          // All loads of the chunk are issued before anything waits on them; slots
+          // past depth_count re-read the last valid slot and get weight zero.
+          u32x4 kv[kDepthChunk], vv[kDepthChunk];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              float s = -INFINITY;
-              if (i0 + i < L) {
-                u32x4 kv = *(const u32x4*)(kd + (size_t)(i0 + i) * C::kRowBytes);
-                float a = dot2_bf16(qv[0], kv[0], 0.f);
-                a = dot2_bf16(qv[1], kv[1], a);
-                a = dot2_bf16(qv[2], kv[2], a);
-                a = dot2_bf16(qv[3], kv[3], a);
-                s = a;
-              }
-              sc[i] = s;
-            }
+          for (int i = 0; i < kDepthChunk; ++i)
+            kv[i] = *(const u32x4*)(kd + (size_t)min(i0 + i, L - 1) * C::kRowBytes);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              sc[i] = group_sum<LPR>(sc[i]);
-              mx = fmaxf(mx, sc[i]);
-            }
-            float al = fast_exp2((m - mx) * c2);
-            float mc = mx * c2;
-            m = mx;
-            l *= al;
+          for (int i = 0; i < kDepthChunk; ++i)
+            vv[i] = *(const u32x4*)(vd + (size_t)min(i0 + i, L - 1) * C::kRowBytes);
+          float sc[kDepthChunk];
+          float mx = m;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) o[k] *= al;
+          for (int i = 0; i < kDepthChunk; ++i) {
+            float a = dot2_bf16(qv[0], kv[i][0], 0.f);
+            a = dot2_bf16(qv[1], kv[i][1], a);
+            a = dot2_bf16(qv[2], kv[i][2], a);
+            a = dot2_bf16(qv[3], kv[i][3], a);
+            a = group_sum<LPR>(a);
+            sc[i] = (i0 + i < L) ? a : -INFINITY;
+            mx = fmaxf(mx, sc[i]);
+          }
+          const float al = fast_exp2((m - mx) * c2);
+          const float mc = mx * c2;
+          m = mx;
+          l *= al;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              if (i0 + i < L) {
-                float pw = fast_exp2(sc[i] * c2 - mc);
-                l += pw;
-                u32x4 vv = *(const u32x4*)(vd + (size_t)(i0 + i) * C::kRowBytes);
+          for (int k = 0; k < 8; ++k) o[k] *= al;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                  o[2 * k] += pw * bf16_lo(vv[k]);
-                  o[2 * k + 1] += pw * bf16_hi(vv[k]);
-                }
-              }
+          for (int i = 0; i < kDepthChunk; ++i) {
+            const float pw = fast_exp2(sc[i] * c2 - mc);
+            l += pw;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              o[2 * k] += pw * bf16_lo(vv[i][k]);
+              o[2 * k + 1] += pw * bf16_hi(vv[i][k]);
             }
           }
         }
-        {
-          float inv = 1.0f / l;
-          u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
-                      pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
-          *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
-          if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
-        }
+      }
+      if (t < T) {
+        const float inv = 1.0f / l;
+        u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
+                    pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
+        *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
+        if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
