@@ -10,7 +10,8 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmoda.so")
+# MODA_LIB_PATH points at another build of the same library (e.g. an experiment)
+LIB_PATH = os.environ.get("MODA_LIB_PATH") or os.path.join(HERE, "libmoda.so")
 
 MODA_F32, MODA_BF16 = 0, 1
 EXPORTS = ("moda_attn_fwd", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd",

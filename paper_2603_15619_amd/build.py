@@ -28,9 +28,44 @@ def _compile(src):
     return obj
 
 
+# Sources whose inline assembly owns accumulation registers a128..a255 by name (see
+# csrc/gen_acc_regs.py).  The compiler is not told that they hold live values, so the
+# build verifies on the generated assembly that it never touches them itself.
+NAMED_ACC_SOURCES = ("moda_fwd_bf16.hip",)
+FIRST_NAMED_ACC = 128
+
+
+def check_named_acc_registers(src) -> None:
+    import re
+
+    asm = os.path.join(OBJ, os.path.basename(src)[:-4] + ".s")
+    subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", asm], check=True,
+                   stderr=subprocess.DEVNULL)
+    in_asm = False
+    pat = re.compile(r"\ba(?:\[(\d+):(\d+)\]|(\d+))\b")
+    for n, line in enumerate(open(asm), 1):
+        if "#ASMSTART" in line:
+            in_asm = True
+            continue
+        if "#ASMEND" in line:
+            in_asm = False
+            continue
+        code = line.split(";")[0]
+        if in_asm or not code.strip() or code.lstrip().startswith("."):
+            continue
+        for m in pat.finditer(code):
+            hi = int(m.group(2) or m.group(3))
+            if hi >= FIRST_NAMED_ACC:
+                raise RuntimeError("%s:%d: compiler-allocated use of a%d collides with the named "
+                                   "accumulation registers: %s" % (asm, n, hi, line.strip()))
+
+
 def build_libmoda() -> str:
     """Always recompiles every source, then links.  Returns the library path."""
     os.makedirs(OBJ, exist_ok=True)
+    for src in sources():
+        if os.path.basename(src) in NAMED_ACC_SOURCES:
+            check_named_acc_registers(src)
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, sources()))
     tmp = LIB + ".tmp.%d" % os.getpid()

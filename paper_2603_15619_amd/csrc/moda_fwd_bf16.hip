@@ -2,17 +2,18 @@
 //
 // One workgroup = 4 waves = one tile of 256 queries of one (b, h); each wave owns
 // 64 queries.  Sequence K/V tiles of 64 keys are copied global -> LDS without
-// passing through registers (double buffered) and consumed by
-// v_mfma_f32_32x32x16_bf16:
+// passing through registers, into rings of 4 (K) and 3 (V) stages, two iterations
+// ahead of their use, and consumed by v_mfma_f32_32x32x16_bf16:
 //   S^T = K Q^T   (keys on the MFMA M axis, queries on N): a lane then holds 16
 //                 scores of ONE query per 32x32 block, so the row max / row sum
 //                 are in-lane reductions plus one exchange with lane ^ 32;
 //   O^T += V^T P^T with P^T taken straight from the S^T accumulators (no layout
 //                 round trip); the V^T operand comes from ds_read_b64_tr_b16.
-// The key loop is software pipelined: while the vector ALUs exponentiate tile kt,
-// the matrix pipe accumulates O += P V of tile kt-1.  The output accumulators and
-// the resident Q fragments sit in named accumulation registers (moda_acc_regs.inc),
-// the score tiles in ordinary vector registers.
+// The key loop is software pipelined so that the matrix pipe never waits for the
+// vector ALUs: while tile kt-1's P V and tile kt+1's K Q^T run on the matrix pipe,
+// the vector ALUs take the row max of tile kt and exponentiate it, a fixed slice
+// after every MFMA.  The output accumulators and the resident Q fragments sit in
+// named accumulation registers (moda_acc_regs.inc), score tiles in vector registers.
 // Tiles above the diagonal are never loaded; only the diagonal tile is masked
 // (Algorithm 1's split into fully visible and boundary blocks).
 // After the sequence loop the accumulators pass through LDS into a row-major
@@ -38,6 +39,8 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kQPerWave = 64;
 constexpr int kBM = kWaves * kQPerWave;  // 256 queries per workgroup
 constexpr int kBN = 64;                  // keys per LDS tile
+constexpr int kStagesK = 4;              // LDS ring depth for K tiles
+constexpr int kStagesV = 3;              // LDS ring depth for V tiles
 constexpr int kDepthChunk = 16;          // depth slots whose loads are in flight together
 
 template <int D>
@@ -51,6 +54,11 @@ struct FwdCfg {
   static constexpr int kXRow = D * 4 + 16;
   static constexpr int kXWave = 32 * kXRow + 32 * 8;  // + (m, l) per row
   static constexpr int kXBytes = kWaves * kXWave;
+  static constexpr int kVBase = kStagesK * kTileBytes;  // V ring follows the K ring
+  static constexpr int kRingBytes = (kStagesK + kStagesV) * kTileBytes;
+  static constexpr int kLds = kRingBytes > kXBytes ? kRingBytes : kXBytes;
+  static constexpr int kRowsPerInst = 64 / kChunks;                 // tile rows per wave copy instruction
+  static constexpr int kInstPerWave = kBN / kRowsPerInst / kWaves;  // copy instructions per wave per tile
 };
 
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
@@ -64,13 +72,31 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
-typedef const __attribute__((address_space(1))) void* gbl_ptr;
-
-// Wait until every global->LDS transfer this wave has issued is complete.
-__device__ __forceinline__ void wait_all_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Nothing may be moved across this point by the instruction scheduler.
 #define MODA_PIN() __builtin_amdgcn_sched_barrier(0)
+// Keeps the computation of x where it is written: the empty volatile statement "uses"
+// x there, and volatile statements (the MFMAs among them) are never reordered, so
+// the compiler can neither sink the arithmetic below the following MFMAs nor hoist it.
+#define MODA_ANCHOR(x) asm volatile("" : "+v"(x))
+// n+1 idle issue slots (n <= 15)
+#define MODA_NOP(n) asm volatile("s_nop " #n ::: "memory")
+
+// 16 bytes per lane, global -> LDS, no register staging: lane i's bytes land at
+// lds_addr + 16 i.  Issued through inline assembly so that the compiler does not
+// serialise later LDS reads of OTHER ring stages against it; completion is awaited
+// explicitly (s_waitcnt vmcnt) before the barrier that publishes the stage.
+__device__ __forceinline__ void copy16_to_lds(const char* gbase, int voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(gbase)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_copies_but() {  // all but the N most recent copies are complete
+  static_assert(N >= 0 && N < 16, "vmcnt immediate");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
 
 // LDS layout of a K or V tile: row r (one key) is kRowBytes long; its 16-byte chunks
 // are permuted by an XOR with the row index so that fragment reads spread over all
@@ -80,8 +106,8 @@ __device__ __forceinline__ void wait_all_vmem() { __builtin_amdgcn_s_waitcnt(0x0
 //           conflict free.
 //   V tile: the 32-byte pair (c >> 1) sits at pair position (c >> 1) ^ (r & (chunks/2-1));
 //           the transposing read (16 lanes read 4 rows x 32 B) is then conflict free.
-// Every fragment address below is (per-lane base ^ constant) + constant, so the
-// second constant rides in the instructions' immediate offset.
+// Every fragment address below is (per-lane base ^ constant) + stage offset + constant;
+// the last constant rides in the instructions' immediate offset.
 template <int D>
 struct FragBase {
   int k[FwdCfg<D>::kDSteps];   // K: lane base ^ (st << 5)
@@ -103,11 +129,12 @@ struct FragBase {
   }
 };
 
-// K fragment idx = st*2 + kb: 32 keys x 16 channels; this lane reads 8 channels of one key.
+// K fragment IDX = st*2 + kb: 32 keys x 16 channels; this lane reads 8 channels of one key.
+// `stage` = smem + byte offset of the ring stage.
 template <int D, int IDX>
-__device__ __forceinline__ i32x4 read_kfrag(const unsigned char* kbuf, const FragBase<D>& fb) {
+__device__ __forceinline__ i32x4 read_kfrag(const unsigned char* stage, const FragBase<D>& fb) {
   constexpr int st = IDX >> 1, kb = IDX & 1;
-  return *(const i32x4*)(kbuf + fb.k[st] + kb * 32 * FwdCfg<D>::kRowBytes);
+  return *(const i32x4*)(stage + fb.k[st] + kb * 32 * FwdCfg<D>::kRowBytes);
 }
 
 // V^T fragment F = ks*kDBlocks + db of a 64-key tile: 16 keys x 32 channels.
@@ -116,10 +143,10 @@ __device__ __forceinline__ i32x4 read_kfrag(const unsigned char* kbuf, const Fra
 // 0..7 (lanes < 32) are keys {0..3, 8..11} of the 16-key group and slots 8..15
 // (lanes >= 32) keys {4..7, 12..15}: how the S^T accumulators hold P^T.
 template <int D, int F>
-__device__ __forceinline__ i32x4 read_vfrag(const unsigned char* vbuf, const FragBase<D>& fb) {
+__device__ __forceinline__ i32x4 read_vfrag(const unsigned char* stage, const FragBase<D>& fb) {
   constexpr int DB = FwdCfg<D>::kDBlocks;
   constexpr int ks = F / DB, db = F % DB;
-  const unsigned char* a0 = vbuf + fb.v[db] + ks * 16 * FwdCfg<D>::kRowBytes;
+  const unsigned char* a0 = stage + fb.v[db] + ks * 16 * FwdCfg<D>::kRowBytes;
   const unsigned char* a1 = a0 + 8 * FwdCfg<D>::kRowBytes;
   s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
   s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a1);
@@ -135,89 +162,136 @@ struct STile {
 struct PTile {
   i32x4 a[2][2][2];  // [key block of 32][16-key half][query block]
 };
+// The first fragments of the next matrix phase, read ahead of it.
+struct Pre3 {
+  i32x4 f[3];
+};
 
-// S^T = K Q^T for a 64-key tile: 4 * kDSteps MFMAs, K fragments prefetched 3 ahead.
-// The hardware does not interlock a matrix result against a vector-ALU reader, so
-// the function ends with enough wait states for the last MFMA (8 passes) to retire.
-template <int D>
-__device__ __forceinline__ void qk_tile(STile& s, const unsigned char* kbuf, const FragBase<D>& fb) {
-  constexpr int NF = FwdCfg<D>::kDSteps * 2;
-  i32x4 kf[NF];
-  kf[0] = read_kfrag<D, 0>(kbuf, fb);
-  kf[1] = read_kfrag<D, 1>(kbuf, fb);
-  kf[2] = read_kfrag<D, 2>(kbuf, fb);
-  static_for<NF>([&](auto F) {
-    constexpr int f = decltype(F)::value;
-    constexpr int st = f >> 1, kb = f & 1;
-    if constexpr (f + 3 < NF) kf[f + 3] = read_kfrag<D, (f + 3 < NF ? f + 3 : 0)>(kbuf, fb);
-    if constexpr (st == 0) {
-      mfma_s_init<st>(s.a[kb][0], kf[f]);
-      mfma_s_init<8 + st>(s.a[kb][1], kf[f]);
-    } else {
-      mfma_s_acc<st>(s.a[kb][0], kf[f]);
-      mfma_s_acc<8 + st>(s.a[kb][1], kf[f]);
-    }
-    MODA_PIN();
-  });
-  asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-  MODA_PIN();
+// Values that are not produced on some control path are set to zero there, so that
+// the compiler does not have to keep their stale contents alive.
+__device__ __forceinline__ void clear(STile& s) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s.a[kb][nb][i] = 0.f;
+}
+__device__ __forceinline__ void clear(PTile& t) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) t.a[kb][hf][nb] = (i32x4){0, 0, 0, 0};
+}
+__device__ __forceinline__ void clear(Pre3& t) {
+  t.f[0] = t.f[1] = t.f[2] = (i32x4){0, 0, 0, 0};
 }
 
-// exp2 of two adjacent scores: pair q of a tile, q = kb*16 + nb*8 + j.
+// exp2 of two adjacent scores: pair Q of a tile, Q = kb*16 + nb*8 + j.
 template <int Q>
 __device__ __forceinline__ void exp_pair(const STile& s, PTile& pt, const float (&mc)[2],
                                          float (&l_run)[2], float c2) {
   constexpr int kb = Q >> 4, nb = (Q >> 3) & 1, j = Q & 7;
   const float e0 = fast_exp2(s.a[kb][nb][2 * j] * c2 - mc[nb]);
   const float e1 = fast_exp2(s.a[kb][nb][2 * j + 1] * c2 - mc[nb]);
-  l_run[nb] += e0 + e1;
-  pt.a[kb][j >> 2][nb][j & 3] = (int)pack_bf16(e0, e1);
+  float l = l_run[nb] + (e0 + e1);
+  int pk = (int)pack_bf16(e0, e1);
+  MODA_ANCHOR(l);
+  MODA_ANCHOR(pk);
+  l_run[nb] = l;
+  pt.a[kb][j >> 2][nb][j & 3] = pk;
 }
 
-// O^T += V^T P^T over a whole tile (8 * kDBlocks MFMAs), optionally interleaved with
-// the exponentiation of the NEXT tile's scores: after every MFMA a fixed slice of the
-// vector-ALU work is issued and pinned there, so both pipes stay busy.
+// ---- matrix phase 1: S^T(next) = K Q^T over one 64-key tile (4*kDSteps MFMAs), with
+// exp2 of the CURRENT tile's second key block (pairs 16..31) spread between the MFMAs
+// when WITH_EXP.  `pre` holds K fragments 0..2, read before the call.  The hardware
+// does not interlock a matrix result against a vector-ALU reader: the caller keeps
+// at least 12 issue slots between the end of this function and the first read of
+// `nxt` (an MFMA of the next phase counts 8).
 template <int D, bool WITH_EXP>
-__device__ __forceinline__ void pv_tile(const unsigned char* vbuf, const PTile& pin, const STile& s,
-                                        PTile& pout, const float (&mc)[2], float (&l_run)[2],
-                                        float c2, const FragBase<D>& fb) {
-  constexpr int DB = FwdCfg<D>::kDBlocks;
-  constexpr int NF = 4 * DB;  // V fragments per tile
-  constexpr int NM = NF * 2;  // MFMAs per tile
-  i32x4 vf[NF];
-  vf[0] = read_vfrag<D, 0>(vbuf, fb);
-  vf[1] = read_vfrag<D, 1>(vbuf, fb);
-  vf[2] = read_vfrag<D, 2>(vbuf, fb);
+__device__ __forceinline__ void qk_phase(STile& nxt, const unsigned char* kstage, const Pre3& pre,
+                                         const i32x4 (&qf)[2][FwdCfg<D>::kDSteps], const STile& cur,
+                                         PTile& pcur, const float (&mc)[2], float (&l_run)[2],
+                                         float c2, const FragBase<D>& fb) {
+  constexpr int NF = FwdCfg<D>::kDSteps * 2;
+  constexpr int NM = NF * 2;
+  i32x4 kf[NF];
+  kf[0] = pre.f[0];
+  kf[1] = pre.f[1];
+  kf[2] = pre.f[2];
   static_for<NF>([&](auto F) {
     constexpr int f = decltype(F)::value;
-    constexpr int ks = f / DB, db = f % DB;
-    constexpr int kb = ks >> 1, hf = ks & 1;
-    if constexpr (f + 3 < NF) vf[f + 3] = read_vfrag<D, (f + 3 < NF ? f + 3 : 0)>(vbuf, fb);
+    constexpr int st = f >> 1, kb = f & 1;
+    if constexpr (f + 3 < NF) kf[f + 3] = read_kfrag<D, (f + 3 < NF ? f + 3 : 0)>(kstage, fb);
     static_for<2>([&](auto NB) {
       constexpr int nb = decltype(NB)::value;
-      mfma_o<db * 2 + nb>(vf[f], pin.a[kb][hf][nb]);
+      if constexpr (st == 0) mfma_s_init(nxt.a[kb][nb], kf[f], qf[nb][st]);
+      else mfma_s_acc(nxt.a[kb][nb], kf[f], qf[nb][st]);
       if constexpr (WITH_EXP) {
-        constexpr int m = f * 2 + nb;             // MFMA index
-        constexpr int lo = (m * 32) / NM;         // exp pairs done before it
-        constexpr int up = ((m + 1) * 32) / NM;   // ... and after it
-        static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(s, pout, mc, l_run, c2); });
+        constexpr int m = f * 2 + nb;
+        constexpr int lo = 16 + (m * 16) / NM, up = 16 + ((m + 1) * 16) / NM;
+        static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
       }
       MODA_PIN();
     });
   });
 }
 
+// ---- matrix phase 2: O^T += V^T P^T over one 64-key tile, V fragments FIRST..LAST-1
+// (2 MFMAs each).  MODE 0: nothing else.  MODE 1 (head, fragments of the first 16
+// keys): the row max of the current score tile is taken between the MFMAs, starting
+// after the second one (see qk_phase).  MODE 2 (tail): exp2 of the current tile's
+// first key block (pairs 0..15) is spread between the MFMAs.
+template <int D, int FIRST, int LAST, int MODE>
+__device__ __forceinline__ void pv_phase(const unsigned char* vstage, i32x4 (&vf)[4 * FwdCfg<D>::kDBlocks],
+                                         const PTile& pin, const STile& s, PTile& pout,
+                                         const float (&mc)[2], float (&l_run)[2], float (&mx)[2],
+                                         float c2, const FragBase<D>& fb) {
+  constexpr int DB = FwdCfg<D>::kDBlocks;
+  constexpr int NF = 4 * DB;
+  constexpr int NM = (LAST - FIRST) * 2;  // MFMAs in this call
+  float vmax[2][2];                        // MODE 1: partial maxima [nb][2 chains]
+  static_for<LAST - FIRST>([&](auto FI) {
+    constexpr int f = FIRST + decltype(FI)::value;
+    constexpr int ks = f / DB, db = f % DB;
+    constexpr int kb = ks >> 1, hf = ks & 1;
+    if constexpr (f + 3 < NF) vf[f + 3] = read_vfrag<D, (f + 3 < NF ? f + 3 : 0)>(vstage, fb);
+    static_for<2>([&](auto NB) {
+      constexpr int nb = decltype(NB)::value;
+      mfma_o<db * 2 + nb>(vf[f], pin.a[kb][hf][nb]);
+      constexpr int m = (f - FIRST) * 2 + nb;  // MFMA index within this call
+      if constexpr (MODE == 1 && m >= 1) {
+        // 64 score registers (2 nb x 32) folded 3 at a time: 32 max3 steps spread over NM-1 slots
+        constexpr int lo = ((m - 1) * 32) / (NM - 1), up = (m * 32) / (NM - 1);
+        static_for<up - lo>([&](auto Z) {
+          constexpr int z = lo + decltype(Z)::value;      // step: nb2 = z / 16, within = z % 16
+          constexpr int nb2 = z >> 4, w = z & 15;         // step w folds registers 2w, 2w+1 of the 32
+          constexpr int kb2 = w >> 3, i0 = (w & 7) * 2;
+          constexpr int ch = w & 1;                        // two independent chains per nb
+          if constexpr (w < 2) vmax[nb2][ch] = fmaxf(s.a[kb2][nb2][i0], s.a[kb2][nb2][i0 + 1]);
+          else vmax[nb2][ch] = fmaxf(fmaxf(vmax[nb2][ch], s.a[kb2][nb2][i0]), s.a[kb2][nb2][i0 + 1]);
+          MODA_ANCHOR(vmax[nb2][ch]);
+        });
+      }
+      if constexpr (MODE == 2) {
+        constexpr int lo = (m * 16) / NM, up = ((m + 1) * 16) / NM;
+        static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(s, pout, mc, l_run, c2); });
+      }
+      MODA_PIN();
+    });
+  });
+  if constexpr (MODE == 1) {
+    mx[0] = pair_max(fmaxf(vmax[0][0], vmax[0][1]));
+    mx[1] = pair_max(fmaxf(vmax[1][0], vmax[1][1]));
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p) {
   using C = FwdCfg<D>;
-  // Separate LDS objects per buffer: the compiler then knows that a fragment read of
-  // one buffer does not depend on an in-flight global->LDS copy into another, and
-  // does not make the read wait for it.
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k0[C::kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k1[C::kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_v0[C::kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_v1[C::kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_x[C::kXBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -242,8 +316,8 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   const char* Kb = (const char*)p.Kseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
   const char* Vb = (const char*)p.Vseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
 
-  // ---- Q fragments (MFMA B operand of S^T = K Q^T) into their named registers;
-  //      fragment index = nb*8 + st
+  // ---- Q fragments (MFMA B operand of S^T = K Q^T), resident in accumulation registers
+  i32x4 qf[2][C::kDSteps];
   {
     i32x4 qtmp[2][C::kDSteps];  // all loads are issued before the first one is consumed
 #pragma unroll
@@ -254,13 +328,10 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
         qtmp[nb][st] = *(const i32x4*)(Qb + (size_t)row * C::kRowBytes + st * 32 + hi * 16);
     }
     MODA_PIN();
-    static_for<2>([&](auto NB) {
-      constexpr int nb = decltype(NB)::value;
-      static_for<C::kDSteps>([&](auto ST) {
-        constexpr int st = decltype(ST)::value;
-        set_q<nb * 8 + st>(qtmp[nb][st]);
-      });
-    });
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int st = 0; st < C::kDSteps; ++st) qf[nb][st] = to_acc(qtmp[nb][st]);
   }
   static_for<C::kDBlocks * 2>([&](auto OB) { zero_o<decltype(OB)::value>(); });
 
@@ -273,15 +344,12 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   const int wave_last = p.causal ? min(nt - 1, qw0 / kBN) : nt - 1;
   const float c2 = p.scale_log2;
 
-  // ---- global -> LDS transfers of one K or V tile (no register staging).  One
-  // wave instruction moves 1 KB: lane i's 16 bytes land at LDS base + 16 i, so the
-  // chunk permutation is applied by choosing which global chunk each lane fetches.
-  constexpr int kRowsPerInst = 64 / C::kChunks;              // tile rows per wave instruction
-  constexpr int kInstPerWave = kBN / kRowsPerInst / kWaves;  // instructions per wave per tile
-  int k_goff[kInstPerWave], v_goff[kInstPerWave], ld_row[kInstPerWave];
+  // ---- global -> LDS copies of one K or V tile.  One wave instruction moves 1 KB,
+  // so the chunk permutation is applied by choosing which global chunk each lane fetches.
+  int k_goff[C::kInstPerWave], v_goff[C::kInstPerWave], ld_row[C::kInstPerWave];
 #pragma unroll
-  for (int i = 0; i < kInstPerWave; ++i) {
-    const int r = (wave * kInstPerWave + i) * kRowsPerInst + lane / C::kChunks;
+  for (int i = 0; i < C::kInstPerWave; ++i) {
+    const int r = (wave * C::kInstPerWave + i) * C::kRowsPerInst + lane / C::kChunks;
     const int pc = lane % C::kChunks;  // chunk position this lane fills
     const int kc = pc ^ (r & (C::kChunks - 1));
     const int vc = (((pc >> 1) ^ (r & (C::kChunks / 2 - 1))) << 1) | (pc & 1);
@@ -289,20 +357,26 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     k_goff[i] = r * C::kRowBytes + kc * 16;
     v_goff[i] = r * C::kRowBytes + vc * 16;
   }
-  auto issue_tile = [&](const char* gbase, int kt, unsigned char* lbuf, const int (&goff)[kInstPerWave]) {
+  const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
+  auto issue_tile = [&](const char* gbase, int kt, int stage_off, const int (&goff)[C::kInstPerWave]) {
     const char* gt = gbase + (size_t)kt * C::kTileBytes;
     const int valid = T - kt * kBN;  // rows of this tile that exist
+    if (valid >= kBN) {
 #pragma unroll
-    for (int i = 0; i < kInstPerWave; ++i) {
-      unsigned char* ldst = lbuf + (wave * kInstPerWave + i) * kRowsPerInst * C::kRowBytes;
-      int off = goff[i];
-      if (valid < kBN) {  // ragged last tile: rows past the end re-read the last row (masked later)
+      for (int i = 0; i < C::kInstPerWave; ++i)
+        copy16_to_lds(gt, goff[i], smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
+    } else {
+      // ragged last tile: rows past the end re-read the last row (their keys are masked later)
+#pragma unroll
+      for (int i = 0; i < C::kInstPerWave; ++i) {
         const int r = min(ld_row[i], valid - 1);
-        off += (r - ld_row[i]) * C::kRowBytes;
+        copy16_to_lds(gt, goff[i] + (r - ld_row[i]) * C::kRowBytes,
+                      smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
       }
-      __builtin_amdgcn_global_load_lds((gbl_ptr)(gt + off), (lds_ptr)ldst, 16, 0, 0);
     }
   };
+  auto k_stage_off = [&](int kt) { return (kt % kStagesK) * C::kTileBytes; };
+  auto v_stage_off = [&](int kt) { return C::kVBase + ((kt + kStagesV) % kStagesV) * C::kTileBytes; };
 
   auto mask_tile = [&](STile& s, int kt) {
     const int k0 = kt * kBN;
@@ -319,17 +393,23 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
         }
     }
   };
+  auto needs_mask = [&](int kt) { return (p.causal && kt * kBN + kBN - 1 > qw0) || (kt * kBN + kBN > T); };
 
-  // ---- software pipeline over key tiles.  Iteration kt computes S = K Q^T of tile
-  // kt on the matrix pipe, then exponentiates it on the vector ALUs WHILE the matrix
-  // pipe accumulates O += P V of tile kt-1 (P of one tile is carried to the next
-  // iteration as packed bf16).  The reference max is only raised when some row's tile
-  // max exceeds it by more than 2^8 in the exp2 domain; P may then exceed 1 (bounded
-  // by 256), which fp32 sums and bf16 P hold without loss, and the final division is
-  // unchanged.  Raising it is the rare path: the pending P V is flushed first, then
-  // the accumulators are rescaled.
   FragBase<D> fb;
   fb.init(lane);
+  const float zero2[2] = {0.f, 0.f};
+  float mx[2] = {0.f, 0.f};
+
+  // ---- prologue: fill the rings, zero the V stage that stands in for "tile -1"
+  // (its P is zero too, but 0 * garbage could be NaN), S(0) = K(0) Q^T.
+  for (int j = 0; j < kStagesK && j < nt; ++j) issue_tile(Kb, j, k_stage_off(j), k_goff);
+  for (int j = 0; j < kStagesV - 1 && j < nt; ++j) issue_tile(Vb, j, v_stage_off(j), v_goff);
+  for (int i = tid * 16; i < C::kTileBytes; i += kThreads * 16)
+    *(i32x4*)(smem + v_stage_off(-1) + i) = (i32x4){0, 0, 0, 0};
+  wait_copies_but<0>();
+  __syncthreads();
+
+  STile sA, sB;
   PTile pA, pB;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -337,45 +417,48 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) pA.a[kb][hf][nb] = pB.a[kb][hf][nb] = (i32x4){0, 0, 0, 0};
-  const float zero2[2] = {0.f, 0.f};
+  Pre3 kpre, vpre;
+  {
+    const unsigned char* ks0 = smem + k_stage_off(0);
+    kpre.f[0] = read_kfrag<D, 0>(ks0, fb);
+    kpre.f[1] = read_kfrag<D, 1>(ks0, fb);
+    kpre.f[2] = read_kfrag<D, 2>(ks0, fb);
+    qk_phase<D, false>(sA, ks0, kpre, qf, sA, pA, zero2, l_run, c2, fb);
+    MODA_PIN();
+    MODA_NOP(15);
+    if (wave_last == 0 && needs_mask(0)) mask_tile(sA, 0);
+    const unsigned char* vs = smem + v_stage_off(-1);
+    vpre.f[0] = read_vfrag<D, 0>(vs, fb);
+    vpre.f[1] = read_vfrag<D, 1>(vs, fb);
+    vpre.f[2] = read_vfrag<D, 2>(vs, fb);
+  }
 
-  issue_tile(Kb, 0, lds_k0, k_goff);
-  // One pipeline iteration; `pin` holds P of tile kt-1, `pout` receives P of tile kt.
-  auto iteration = [&](int kt, auto parity, const PTile& pin, PTile& pout) {
-    constexpr int PAR = decltype(parity)::value;  // kt & 1, known at compile time
-    unsigned char* const k_cur = PAR ? lds_k1 : lds_k0;  // K tile kt
-    unsigned char* const k_nxt = PAR ? lds_k0 : lds_k1;  // K tile kt+1
-    unsigned char* const v_cur = PAR ? lds_v1 : lds_v0;  // V tile kt
-    unsigned char* const v_prv = PAR ? lds_v0 : lds_v1;  // V tile kt-1
-    // K tile kt and V tile kt-1 were issued one iteration ago
-    wait_all_vmem();
-    __syncthreads();
-    // every wave is past iteration kt-1: K tile kt-1 and V tile kt-2 are dead
-    if (kt + 1 < nt) issue_tile(Kb, kt + 1, k_nxt, k_goff);
-    if (kt < nt) issue_tile(Vb, kt, v_cur, v_goff);
-
+  // ---- steady state.  Step kt (scores of tile kt are in `cur`, P of tile kt-1 in `pprev`):
+  //   matrix pipe : O += P V (tile kt-1)            | S(next) = K Q^T (tile kt+1)
+  //   vector ALUs : row max of tile kt, exp2 of its | exp2 of its second key block
+  //                 first key block                 |
+  //   in between  : wait for the copies issued two steps ago, barrier, issue the copies
+  //                 of K tile kt+4 and V tile kt+2 into the stages just vacated.
+  // The reference max is only raised when some row's tile max exceeds it by more than
+  // 2^8 in the exp2 domain; P may then exceed 1 (bounded by 256), which fp32 sums and
+  // bf16 P hold without loss, and the final division is unchanged.  Raising it is the
+  // rare path: the pending P V is finished first, then the accumulators are rescaled.
+  auto step = [&](int kt, STile& cur, STile& nxt, const PTile& pprev, PTile& pcur) {
+    constexpr int NFV = 4 * C::kDBlocks;
+    constexpr int HEAD = C::kDBlocks;  // V fragments of the first 16 keys
     if (kt <= wave_last) {
-      STile s;
-      qk_tile<D>(s, k_cur, fb);
-      const int k0 = kt * kBN;
-      if ((p.causal && k0 + kBN - 1 > qw0) || (k0 + kBN > T)) mask_tile(s, kt);
-
-      float mx[2];
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        float v = s.a[0][nb][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) v = fmaxf(v, s.a[kb][nb][i]);
-        mx[nb] = pair_max(v);
-      }
+      const unsigned char* vs = smem + v_stage_off(kt - 1);
+      i32x4 vf[NFV];
+      vf[0] = vpre.f[0];
+      vf[1] = vpre.f[1];
+      vf[2] = vpre.f[2];
+      pv_phase<D, 0, HEAD, 1>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
       const bool raise = (mx[0] - m_run[0]) * c2 > 8.f || (mx[1] - m_run[1]) * c2 > 8.f;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) {
         // Rare path (always taken for the first tile, where m_run = -inf).
-        if (kt > 0) pv_tile<D, false>(v_prv, pin, s, pout, zero2, l_run, c2, fb);
+        pv_phase<D, HEAD, NFV, 0>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
         MODA_PIN();
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // every MFMA above has retired
+        MODA_NOP(15);  // every MFMA above has retired
         float alpha[2];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
@@ -389,29 +472,75 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
           scale_o<ob>(alpha[ob & 1]);
         });
         MODA_PIN();
-        asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // register writes settle before the next MFMA
+        MODA_NOP(7);  // register writes settle before the next MFMA
         const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
-        static_for<32>([&](auto Q) { exp_pair<decltype(Q)::value>(s, pout, mc, l_run, c2); });
+        static_for<16>([&](auto Q) { exp_pair<decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
       } else {
         const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
-        pv_tile<D, true>(v_prv, pin, s, pout, mc, l_run, c2, fb);
+        pv_phase<D, HEAD, NFV, 2>(vs, vf, pprev, cur, pcur, mc, l_run, mx, c2, fb);
       }
+      // (for this wave's last tile the next K tile is not needed; it is read and
+      //  multiplied all the same, which keeps the loop body free of branches)
+      const unsigned char* ksn = smem + k_stage_off(kt + 1);
+      kpre.f[0] = read_kfrag<D, 0>(ksn, fb);
+      kpre.f[1] = read_kfrag<D, 1>(ksn, fb);
+      kpre.f[2] = read_kfrag<D, 2>(ksn, fb);
     } else if (kt == wave_last + 1) {
       // this wave's last tile: only its P V is left
-      STile s;
-      pv_tile<D, false>(v_prv, pin, s, pout, zero2, l_run, c2, fb);
+      const unsigned char* vs = smem + v_stage_off(kt - 1);
+      i32x4 vf[NFV];
+      vf[0] = vpre.f[0];
+      vf[1] = vpre.f[1];
+      vf[2] = vpre.f[2];
+      pv_phase<D, 0, NFV, 0>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
+      clear(kpre);
+      clear(pcur);
+    } else {
+      clear(kpre);
+      clear(pcur);
+    }
+
+    if (kt < nt) {
+      // The copies issued at the previous step (K tile kt+3, V tile kt+1) may still be in
+      // flight; everything older must have landed: K tile kt+2 and V tile kt are read next.
+      const int newer = ((kt + kStagesK - 1 < nt) ? C::kInstPerWave : 0) +
+                        ((kt >= 1 && kt + kStagesV - 2 < nt) ? C::kInstPerWave : 0);
+      if (newer == 2 * C::kInstPerWave) wait_copies_but<2 * C::kInstPerWave>();
+      else if (newer == C::kInstPerWave) wait_copies_but<C::kInstPerWave>();
+      else wait_copies_but<0>();
+      __syncthreads();
+      // every wave is past the first half of step kt: K tile kt and V tile kt-1 are dead
+      if (kt + kStagesK < nt) issue_tile(Kb, kt + kStagesK, k_stage_off(kt + kStagesK), k_goff);
+      if (kt + kStagesV - 1 < nt) issue_tile(Vb, kt + kStagesV - 1, v_stage_off(kt + kStagesV - 1), v_goff);
+    }
+
+    if (kt <= wave_last) {
+      const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
+      qk_phase<D, true>(nxt, smem + k_stage_off(kt + 1), kpre, qf, cur, pcur, mc, l_run, c2, fb);
+      if (kt + 1 == wave_last && needs_mask(kt + 1)) {
+        MODA_PIN();
+        MODA_NOP(15);
+        mask_tile(nxt, kt + 1);
+      }
+      const unsigned char* vs = smem + v_stage_off(kt);
+      vpre.f[0] = read_vfrag<D, 0>(vs, fb);
+      vpre.f[1] = read_vfrag<D, 1>(vs, fb);
+      vpre.f[2] = read_vfrag<D, 2>(vs, fb);
+    } else {
+      clear(nxt);
+      clear(vpre);
     }
   };
   for (int kt = 0; kt <= nt; kt += 2) {
-    iteration(kt, std::integral_constant<int, 0>{}, pA, pB);
-    if (kt + 1 <= nt) iteration(kt + 1, std::integral_constant<int, 1>{}, pB, pA);
+    step(kt, sA, sB, pA, pB);
+    if (kt + 1 <= nt) step(kt + 1, sB, sA, pB, pA);
   }
   MODA_PIN();
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // accumulators final before they are read out
+  MODA_NOP(15);  // accumulators final before they are read out
   __syncthreads();
 
   // ================= epilogue: accumulator layout -> row-major, depth slots, store
-  unsigned char* xw = lds_x + wave * C::kXWave;
+  unsigned char* xw = smem + wave * C::kXWave;
   float* ml = (float*)(xw + 32 * C::kXRow);
   constexpr int LPR = C::kChunks;   // lanes per query row: each owns 8 channels (16 B)
   constexpr int RPS = 64 / LPR;     // query rows per wave step
