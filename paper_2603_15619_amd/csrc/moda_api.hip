@@ -48,7 +48,7 @@ int moda_version(void) { return 100; }
 int moda_kernels_per_call(const moda_shape* s, int which) {
   if (check_shape(s) != MODA_OK || s->B == 0 || s->T == 0) return 0;
   if (which == 0) return 1;
-  return 0;
+  return (s->dtype == MODA_BF16 && s->Hq == s->Hk) ? 3 : 0;
 }
 
 moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
@@ -81,16 +81,42 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
 }
 
 size_t moda_attn_bwd_workspace_bytes(const moda_shape* s) {
-  (void)s;
-  return 0;
+  if (check_shape(s) != MODA_OK) return 0;
+  moda::BwdParams p{};
+  p.B = s->B; p.Hq = s->Hq; p.T = s->T;
+  return moda::bwd_bf16_workspace_bytes(p);
 }
 
-moda_status moda_attn_bwd(const void*, const void*, const void*, const void*, const void*,
-                          const void*, const float*, const void*, void*, void*, void*, void*,
-                          void*, void*, size_t, const moda_shape* s, void*) {
+moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                          const void* Vdepth, const void* O, const float* LSE, const void* dO,
+                          void* dQ, void* dKseq, void* dVseq, void* dKdepth, void* dVdepth,
+                          void* workspace, size_t workspace_bytes, const moda_shape* s,
+                          void* hip_stream) {
   moda_status st = check_shape(s);
   if (st != MODA_OK) return st;
-  return MODA_ERR_UNSUPPORTED;  // backward kernels are not built yet
+  // this build's backward: bf16, one query head per key/value head
+  if (s->dtype != MODA_BF16 || s->Hq != s->Hk) return MODA_ERR_UNSUPPORTED;
+  if (s->B == 0 || s->T == 0) return MODA_OK;
+  if (!Q || !Kseq || !Vseq || !O || !LSE || !dO || !dQ || !dKseq || !dVseq) return MODA_ERR_NULL;
+  if (s->depth_count > 0 && (!Kdepth || !Vdepth)) return MODA_ERR_NULL;
+  if (s->depth_alloc > 0 && (!dKdepth || !dVdepth)) return MODA_ERR_NULL;
+  const void* ptrs[] = {Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, dO, dQ, dKseq, dVseq, dKdepth, dVdepth, workspace};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MODA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < moda_attn_bwd_workspace_bytes(s)) return MODA_ERR_WORKSPACE;
+
+  moda::BwdParams p;
+  p.Q = Q; p.Kseq = Kseq; p.Vseq = Vseq; p.Kdepth = Kdepth; p.Vdepth = Vdepth;
+  p.O = O; p.LSE = LSE; p.dO = dO;
+  p.dQ = dQ; p.dKseq = dKseq; p.dVseq = dVseq; p.dKdepth = dKdepth; p.dVdepth = dVdepth;
+  p.delta = static_cast<float*>(workspace);
+  p.B = s->B; p.Hq = s->Hq; p.Hk = s->Hk; p.T = s->T;
+  p.depth_alloc = s->depth_alloc; p.depth_count = s->depth_count;
+  p.causal = s->causal;
+  p.scale = resolve_scale(s);
+  p.scale_log2 = p.scale * 1.4426950408889634f;
+  hipError_t e = moda::launch_bwd_bf16(p, s->d, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
 }
 
 }  // extern "C"

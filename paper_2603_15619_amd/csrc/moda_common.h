@@ -34,6 +34,29 @@ struct FwdParams {
   int n_qtiles;      // query tiles per (b, h)
 };
 
+// Kernel arguments of the backward pass (bf16, Hq == Hk).
+struct BwdParams {
+  const void* Q;
+  const void* Kseq;
+  const void* Vseq;
+  const void* Kdepth;
+  const void* Vdepth;
+  const void* O;
+  const float* LSE;
+  const void* dO;
+  void* dQ;
+  void* dKseq;
+  void* dVseq;
+  void* dKdepth;
+  void* dVdepth;
+  float* delta;  // workspace: <dO_t, O_t> per row, [B, Hq, T]
+  int B, Hq, Hk, T;
+  int depth_alloc, depth_count;
+  int causal;
+  float scale;
+  float scale_log2;
+};
+
 // Value held by lane (l ^ 32) of the same wave.
 __device__ __forceinline__ float partner32(float x) {
   int xi = __builtin_bit_cast(int, x);

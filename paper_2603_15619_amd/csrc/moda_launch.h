@@ -9,4 +9,8 @@ int fwd_bf16_tile_rows();
 hipError_t launch_fwd_bf16(const FwdParams& p, int d, hipStream_t stream);
 hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream);
 
+// Backward (bf16, Hq == Hk): delta, dK/dV and dQ/depth kernels on `stream`.
+size_t bwd_bf16_workspace_bytes(const BwdParams& p);
+hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream);
+
 }  // namespace moda

@@ -1,0 +1,115 @@
+"""GPU parity: libmoda backward (through the C ABI) against the fp64 CPU oracle.
+
+The backward consumes O and LSE of the library's own forward.  Inputs are bf16;
+gradients come back in bf16 after fp32 accumulation.  Tolerance (per element):
+|got - ref| <= ATOL + RTOL * |ref| with ATOL = RTOL = 2e-2: the output rounding to
+bf16 alone is 2^-9 relative, and P / dS are rounded to bf16 before the matrix
+products, the same budget the forward's 2e-2 on O allows.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moda_ref as R
+from paper_2603_15619_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+ATOL = 2e-2
+RTOL = 2e-2
+NAMES = ("dQ", "dKseq", "dVseq", "dKdepth", "dVdepth")
+
+
+def run_gpu(inp, L, causal=True, scale=None):
+    from paper_2603_15619_amd import moda_attn_bwd, moda_attn_fwd
+
+    O, LSE = moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"],
+                           depth_count=L, causal=causal, scale=scale)
+    grads = moda_attn_bwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], O, LSE,
+                          inp["dO"], depth_count=L, causal=causal, scale=scale)
+    torch.cuda.synchronize()
+    return grads
+
+
+def compare(name, got, ref):
+    got = synth.to_f64(got)
+    assert np.isfinite(got).all(), name
+    err = np.abs(got - ref)
+    worst = float((err - RTOL * np.abs(ref)).max())
+    print("   %-8s max|err| = %.3e  max|ref| = %.3e  worst excess over rtol = %.3e" %
+          (name, err.max(), np.abs(ref).max(), worst), flush=True)
+    assert worst <= ATOL, name
+
+
+def check_full(B, H, T, d, L, seed, causal=True, depth_alloc=None, scale=None):
+    print("bwd case", dict(B=B, H=H, T=T, d=d, L=L, seed=seed, causal=causal, depth_alloc=depth_alloc),
+          flush=True)
+    inp = synth.make_inputs(B, H, H, T, d, L, dtype="bf16", seed=seed, device="cuda",
+                            depth_alloc=depth_alloc, with_dO=True)
+    grads = run_gpu(inp, L, causal, scale)
+    ref = R.bwd(*(synth.to_f64(inp[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth", "dO")),
+                depth_count=L, causal=causal, scale=scale)
+    for name, g, r in zip(NAMES, grads, ref):
+        if r is None:
+            assert g is None
+            continue
+        compare(name, g, r)
+
+
+@pytest.mark.parametrize("T,d,L", [(300, 128, 5), (200, 64, 3), (130, 128, 0), (257, 128, 15),
+                                   (64, 64, 9), (1, 128, 2), (500, 128, 17)])
+def test_bwd_shapes(T, d, L):
+    check_full(2, 2, T, d, L, 300 + T + L)
+
+
+def test_bwd_non_causal_and_slot_stride():
+    check_full(1, 2, 333, 128, 3, 21, causal=False)
+    check_full(1, 2, 300, 128, 4, 22, depth_alloc=6)
+    check_full(1, 3, 260, 64, 2, 23, scale=0.2)
+
+
+def test_bwd_deterministic():
+    inp = synth.make_inputs(1, 2, 2, 400, 128, 7, dtype="bf16", seed=24, device="cuda", with_dO=True)
+    a = run_gpu(inp, 7)
+    b = run_gpu(inp, 7)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_bwd_rejects_unsupported():
+    from paper_2603_15619_amd import MODAError
+
+    inp = synth.make_inputs(1, 4, 2, 64, 128, 2, dtype="bf16", seed=25, device="cuda", with_dO=True)
+    with pytest.raises(MODAError):  # grouped-query backward is not built
+        run_gpu(inp, 2)
+
+
+def test_config5_t256_slice_full():
+    """B=8, H=16, d=128, depth_count=15: the T=256 problem, all five gradients in full."""
+    check_full(8, 16, 256, 128, 15, 4)
+
+
+def test_config5_full_size_sampled():
+    """B=8, H=16, d=128, T=4096, depth_count=15: row-local gradients on sampled rows of
+    every (b, h), and dKseq / dVseq in full for two (b, h) against a full-T oracle."""
+    B, H, T, d, L = 8, 16, 4096, 128, 15
+    inp = synth.make_inputs(B, H, H, T, d, L, dtype="bf16", seed=4, device="cuda", with_dO=True)
+    dQ, dK, dV, dKd, dVd = run_gpu(inp, L)
+    rows = synth.sample_rows(T, n_random=16, edge=4, tile=512, seed=4)
+    ridx = torch.from_numpy(rows.astype(np.int64)).cuda()
+    pick = lambda t: synth.to_f64(t.index_select(2, ridx))
+    rq, rkd, rvd = R.bwd_rows(pick(inp["Q"]), synth.to_f64(inp["Kseq"]), synth.to_f64(inp["Vseq"]),
+                              pick(inp["Kdepth"]), pick(inp["Vdepth"]), pick(inp["dO"]), rows,
+                              depth_count=L)
+    compare("dQ", dQ.index_select(2, ridx), rq)
+    compare("dKdepth", dKd.index_select(2, ridx), rkd)
+    compare("dVdepth", dVd.index_select(2, ridx), rvd)
+    # two (b, h) slabs in full: (0, 0) and (B-1, H-1)
+    for (b, h) in [(0, 0), (B - 1, H - 1)]:
+        sl = lambda t: synth.to_f64(t[b:b + 1, h:h + 1])
+        ref = R.bwd(sl(inp["Q"]), sl(inp["Kseq"]), sl(inp["Vseq"]), sl(inp["Kdepth"]), sl(inp["Vdepth"]),
+                    sl(inp["dO"]), depth_count=L)
+        compare("dKseq[%d,%d]" % (b, h), dK[b:b + 1, h:h + 1], ref[1])
+        compare("dVseq[%d,%d]" % (b, h), dV[b:b + 1, h:h + 1], ref[2])
+    for g in (dQ, dK, dV, dKd, dVd):
+        assert torch.isfinite(g.float()).all()
