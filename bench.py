@@ -29,6 +29,8 @@ WORKLOADS = {
     "long_context_64k": (1, 16, 16, 65536, 128, 15, "bf16"),   # BASELINE configs[2] (the metric's workload)
     "layer_1p5b_4k": (8, 16, 16, 4096, 128, 15, "bf16"),       # BASELINE configs[1]
     "tiny_fp32": (1, 2, 2, 256, 64, 4, "f32"),                 # BASELINE configs[0]
+    "bwd_layer_1p5b_4k": (8, 16, 16, 4096, 128, 15, "bf16"),   # BASELINE configs[4] (backward)
+    "copy_calibration": None,  # plain device copy of known size, for scaling the HBM byte counters
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 vector
 
@@ -36,6 +38,62 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 ve
 def fwd_flops(B, H, T, d, L, causal=True):
     pairs = T * (T + 1) // 2 if causal else T * T
     return 4.0 * d * B * H * (pairs + T * L)
+
+
+def bwd_flops(B, H, T, d, L, causal=True):
+    """10*d per visible pair: five d-length contractions (S, dP, dV, dQ, dK)."""
+    pairs = T * (T + 1) // 2 if causal else T * T
+    return 10.0 * d * B * H * (pairs + T * L)
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
+    profiles/), or None if this workload has not been measured."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        table = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    return table.get("%s/%s" % (workload, kernel))
+
+
+def run_copy_calibration(args):
+    n = 1 << 30  # 4 GiB of fp32 in, 4 GiB out
+    a = torch.ones(n, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    ms, _, _ = time_calls(lambda: b.copy_(a), args.steps, args.warmup)
+    print(json.dumps({"metric": "plain device copy", "bytes_read": 4 * n, "bytes_written": 4 * n,
+                      "ms_per_step": round(ms, 4), "value": round(8 * n / ms / 1e6, 1), "unit": "GB/s",
+                      "steps": args.steps, "warmup": args.warmup}))
+
+
+def run_backward(args, B, Hq, Hk, T, d, L, dtype):
+    from paper_2603_15619_amd import moda_attn_bwd, moda_attn_fwd, synth
+
+    inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=4, device="cuda", with_dO=True)
+    O, LSE = moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], depth_count=L)
+    ws = torch.empty(4 * B * Hq * T + 256, dtype=torch.uint8, device="cuda")
+
+    def run():
+        moda_attn_bwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], O, LSE, inp["dO"],
+                      depth_count=L, workspace=ws)
+
+    ms_step, ms_kernel, ms_min = time_calls(run, args.steps, args.warmup)
+    flops = bwd_flops(B, Hq, T, d, L)
+    esz = 2
+    # reads Q, K, V, O, dO, depth K/V; writes dQ, dK, dV, depth grads
+    alg_bytes = esz * B * T * d * (Hq * 3 + Hk * 2 + Hq + 2 * Hk) + 4.0 * esz * B * Hk * T * L * d
+    print(json.dumps({
+        "metric": "MoDA attn bwd TFLOP/s, 1 GPU", "value": round(flops / (ms_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d H=%d T=%d d=%d depth_count=%d causal bwd (3 kernels per call)" %
+                               (args.workload, B, Hq, T, d, L)},
+        "roofline": {"bound": "hbm", "achieved": round(alg_bytes / (ms_kernel * 1e-3) / 1e9, 1), "peak": 8000.0,
+                     "unit": "GB/s", "frac": round(alg_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0, 4),
+                     "traffic": measured_traffic(args.workload, "bwd"), "call_ms_mean": round(ms_kernel, 4),
+                     "bytes_per_call": alg_bytes, "flops_per_call": flops}}))
 
 
 def time_calls(fn, steps, warmup):
@@ -89,7 +147,7 @@ def main():
     ap.add_argument("--depth-count", type=int, default=None, help="override the workload's depth_count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fa", action="store_true", help="skip the depth_count=0 comparison run")
-    ap.add_argument("--cpu-rows", type=int, default=192)
+    ap.add_argument("--cpu-rows", type=int, default=4096)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (every (b,h) is independent, "
@@ -101,7 +159,11 @@ def main():
 
     from paper_2603_15619_amd import moda_attn_fwd, synth
 
+    if args.workload == "copy_calibration":
+        return run_copy_calibration(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
+    if args.workload.startswith("bwd_"):
+        return run_backward(args, B, Hq, Hk, T, d, L, dtype)
     if args.depth_count is not None:
         L = args.depth_count
     inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=2, device="cuda")
@@ -141,7 +203,8 @@ def main():
                                (args.workload, B, Hq, Hk, T, d, L)},
         "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "achieved": round(achieved, 2),
                      "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": None,
+                     "frac": round(achieved / PEAK_TFLOPS[dtype], 4),
+                     "traffic": measured_traffic(args.workload, "fwd"),
                      "kernel": "moda_fwd_%s_kernel<%d>" % (dtype, d),
                      "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
                      "flops_per_launch": flops},
