@@ -54,7 +54,8 @@ def measured_traffic(workload, kernel):
         table = json.load(open(path))
     except (OSError, ValueError):
         return None
-    return table.get("%s/%s" % (workload, kernel))
+    entry = table.get("%s/%s" % (workload, kernel))
+    return None if entry is None else entry["hbm_bytes"]
 
 
 def run_copy_calibration(args):
