@@ -31,6 +31,7 @@ WORKLOADS = {
     "tiny_fp32": (1, 2, 2, 256, 64, 4, "f32"),                 # BASELINE configs[0]
     "bwd_layer_1p5b_4k": (8, 16, 16, 4096, 128, 15, "bf16"),   # BASELINE configs[4] (backward)
     "copy_calibration": None,  # plain device copy of known size, for scaling the HBM byte counters
+    "sweep": None,             # BASELINE configs[3]: B=4 H=16 d=128, T x depth_count grid
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 vector
 
@@ -66,6 +67,35 @@ def run_copy_calibration(args):
     print(json.dumps({"metric": "plain device copy", "bytes_read": 4 * n, "bytes_written": 4 * n,
                       "ms_per_step": round(ms, 4), "value": round(8 * n / ms / 1e6, 1), "unit": "GB/s",
                       "steps": args.steps, "warmup": args.warmup}))
+
+
+def run_sweep(args):
+    """BASELINE configs[3]: TFLOP/s and depth-segment GB/s per (T, depth_count) point."""
+    from paper_2603_15619_amd import moda_attn_fwd, synth
+
+    B, H, d = 4, 16, 128
+    points = []
+    for T in (1024, 4096, 16384):
+        inp = synth.make_inputs(B, H, H, T, d, 31, dtype="bf16", seed=3, device="cuda")
+        O = torch.empty_like(inp["Q"])
+        LSE = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+        t0 = None
+        for L in (0, 1, 7, 15, 31):
+            kd = None if L == 0 else inp["Kdepth"][:, :, :, :L].contiguous()
+            vd = None if L == 0 else inp["Vdepth"][:, :, :, :L].contiguous()
+            fn = lambda: moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], kd, vd, depth_count=L, out=O, lse=LSE)
+            ms, _, _ = time_calls(fn, args.steps, args.warmup)
+            if L == 0:
+                t0 = ms
+            depth_bytes = 2.0 * B * H * T * L * d * 2
+            points.append({"T": T, "depth_count": L, "ms": round(ms, 4),
+                           "tflops": round(fwd_flops(B, H, T, d, L) / (ms * 1e-3) / 1e12, 1),
+                           "ratio_to_depth0": round(t0 / ms, 4),
+                           "depth_gbps_over_extra_time": round(depth_bytes / ((ms - t0) * 1e-3) / 1e9, 1)
+                           if L and ms > t0 else None,
+                           "depth_gbps_over_call": round(depth_bytes / (ms * 1e-3) / 1e9, 1)})
+    print(json.dumps({"metric": "MoDA attn fwd sweep (B=4 H=16 d=128 bf16 causal)", "steps": args.steps,
+                      "warmup": args.warmup, "points": points}))
 
 
 def run_backward(args, B, Hq, Hk, T, d, L, dtype):
@@ -162,6 +192,8 @@ def main():
 
     if args.workload == "copy_calibration":
         return run_copy_calibration(args)
+    if args.workload == "sweep":
+        return run_sweep(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
     if args.workload.startswith("bwd_"):
         return run_backward(args, B, Hq, Hk, T, d, L, dtype)
