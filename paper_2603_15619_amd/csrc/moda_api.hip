@@ -19,6 +19,10 @@ moda_status check_shape(const moda_shape* s) {
   if (s->dtype != MODA_F32 && s->dtype != MODA_BF16) return MODA_ERR_UNSUPPORTED;
   if (s->d != 64 && s->d != 128) return MODA_ERR_UNSUPPORTED;
   if (!(s->scale == s->scale) || isinf(s->scale)) return MODA_ERR_SHAPE;  // NaN / inf
+  // one (b, h) slab of any tensor must stay below 4 GiB (32-bit buffer offsets)
+  const unsigned long long esz = s->dtype == MODA_BF16 ? 2 : 4;
+  const unsigned long long slots = s->depth_alloc > 0 ? (unsigned long long)s->depth_alloc : 1ull;
+  if ((unsigned long long)s->T * slots * (unsigned long long)s->d * esz >= (1ull << 32)) return MODA_ERR_UNSUPPORTED;
   return MODA_OK;
 }
 

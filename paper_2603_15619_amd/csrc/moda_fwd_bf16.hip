@@ -41,7 +41,10 @@ constexpr int kBM = kWaves * kQPerWave;  // 256 queries per workgroup
 constexpr int kBN = 64;                  // keys per LDS tile
 constexpr int kStagesK = 4;              // LDS ring depth for K tiles
 constexpr int kStagesV = 3;              // LDS ring depth for V tiles
-constexpr int kDepthChunk = 16;          // depth slots whose loads are in flight together
+// cache policy of loads whose data is used exactly once (depth K/V): non-temporal, so
+// that the stream does not push the re-used sequence K/V tiles out of the L2
+constexpr int kStreamOnce = 2;
+constexpr int kDepthChunk = 8;           // depth slots per work item of the depth phase
 
 template <int D>
 struct FwdCfg {
@@ -83,13 +86,26 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 #define MODA_NOP(n) asm volatile("s_nop " #n ::: "memory")
 
 // 16 bytes per lane, global -> LDS, no register staging: lane i's bytes land at
-// lds_addr + 16 i.  Issued through inline assembly so that the compiler does not
-// serialise later LDS reads of OTHER ring stages against it; completion is awaited
-// explicitly (s_waitcnt vmcnt) before the barrier that publishes the stage.
-__device__ __forceinline__ void copy16_to_lds(const char* gbase, int voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+// lds_addr + 16 i.  The source is a raw buffer (base, size in bytes): lanes whose
+// offset voff + soff falls outside it fetch nothing and write zeros, so ragged and
+// non-existent tiles need no special case.  Issued through inline assembly so that
+// the compiler does not serialise later LDS reads of OTHER ring stages against it;
+// completion is awaited explicitly (s_waitcnt vmcnt) before the barrier that
+// publishes the stage.
+__device__ __forceinline__ i32x4 make_raw_buffer(const void* base, unsigned bytes) {
+  const unsigned long long b = (unsigned long long)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(b & 0xffffffffu));
+  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((b >> 32) & 0xffffu));  // stride 0
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;  // 32-bit untyped data
+  return r;
+}
+__device__ __forceinline__ void copy16_to_lds(const i32x4& rsrc, int voff, int soff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
-               : "s"(lds_addr), "v"(voff), "s"(gbase)
+               : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
                : "memory");
 }
 template <int N>
@@ -163,8 +179,9 @@ struct PTile {
   i32x4 a[2][2][2];  // [key block of 32][16-key half][query block]
 };
 // The first fragments of the next matrix phase, read ahead of it.
+constexpr int kAhead = 4;  // fragments read ahead of the MFMA that consumes them
 struct Pre3 {
-  i32x4 f[3];
+  i32x4 f[kAhead];
 };
 
 // Values that are not produced on some control path are set to zero there, so that
@@ -186,7 +203,8 @@ __device__ __forceinline__ void clear(PTile& t) {
       for (int nb = 0; nb < 2; ++nb) t.a[kb][hf][nb] = (i32x4){0, 0, 0, 0};
 }
 __device__ __forceinline__ void clear(Pre3& t) {
-  t.f[0] = t.f[1] = t.f[2] = (i32x4){0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) t.f[i] = (i32x4){0, 0, 0, 0};
 }
 
 // exp2 of two adjacent scores: pair Q of a tile, Q = kb*16 + nb*8 + j.
@@ -210,21 +228,27 @@ __device__ __forceinline__ void exp_pair(const STile& s, PTile& pt, const float 
 // does not interlock a matrix result against a vector-ALU reader: the caller keeps
 // at least 12 issue slots between the end of this function and the first read of
 // `nxt` (an MFMA of the next phase counts 8).
-template <int D, bool WITH_EXP>
+// `hook(integral_constant<m>)` runs after MFMA number m: the caller spreads its
+// global->LDS copy instructions there, one at a time, so that their issue time is
+// hidden behind matrix work as well.
+struct NoHook {
+  template <class I>
+  __device__ __forceinline__ void operator()(I) const {}
+};
+template <int D, bool WITH_EXP, class Hook = NoHook>
 __device__ __forceinline__ void qk_phase(STile& nxt, const unsigned char* kstage, const Pre3& pre,
                                          const i32x4 (&qf)[2][FwdCfg<D>::kDSteps], const STile& cur,
                                          PTile& pcur, const float (&mc)[2], float (&l_run)[2],
-                                         float c2, const FragBase<D>& fb) {
+                                         float c2, const FragBase<D>& fb, Hook hook = Hook{}) {
   constexpr int NF = FwdCfg<D>::kDSteps * 2;
   constexpr int NM = NF * 2;
   i32x4 kf[NF];
-  kf[0] = pre.f[0];
-  kf[1] = pre.f[1];
-  kf[2] = pre.f[2];
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) kf[i] = pre.f[i];
   static_for<NF>([&](auto F) {
     constexpr int f = decltype(F)::value;
     constexpr int st = f >> 1, kb = f & 1;
-    if constexpr (f + 3 < NF) kf[f + 3] = read_kfrag<D, (f + 3 < NF ? f + 3 : 0)>(kstage, fb);
+    if constexpr (f + kAhead < NF) kf[f + kAhead] = read_kfrag<D, (f + kAhead < NF ? f + kAhead : 0)>(kstage, fb);
     static_for<2>([&](auto NB) {
       constexpr int nb = decltype(NB)::value;
       if constexpr (st == 0) mfma_s_init(nxt.a[kb][nb], kf[f], qf[nb][st]);
@@ -234,6 +258,7 @@ __device__ __forceinline__ void qk_phase(STile& nxt, const unsigned char* kstage
         constexpr int lo = 16 + (m * 16) / NM, up = 16 + ((m + 1) * 16) / NM;
         static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
       }
+      hook(std::integral_constant<int, f * 2 + nb>{});
       MODA_PIN();
     });
   });
@@ -257,7 +282,7 @@ __device__ __forceinline__ void pv_phase(const unsigned char* vstage, i32x4 (&vf
     constexpr int f = FIRST + decltype(FI)::value;
     constexpr int ks = f / DB, db = f % DB;
     constexpr int kb = ks >> 1, hf = ks & 1;
-    if constexpr (f + 3 < NF) vf[f + 3] = read_vfrag<D, (f + 3 < NF ? f + 3 : 0)>(vstage, fb);
+    if constexpr (f + kAhead < NF) vf[f + kAhead] = read_vfrag<D, (f + kAhead < NF ? f + kAhead : 0)>(vstage, fb);
     static_for<2>([&](auto NB) {
       constexpr int nb = decltype(NB)::value;
       mfma_o<db * 2 + nb>(vf[f], pin.a[kb][hf][nb]);
@@ -346,34 +371,27 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
 
   // ---- global -> LDS copies of one K or V tile.  One wave instruction moves 1 KB,
   // so the chunk permutation is applied by choosing which global chunk each lane fetches.
-  int k_goff[C::kInstPerWave], v_goff[C::kInstPerWave], ld_row[C::kInstPerWave];
+  int k_goff[C::kInstPerWave], v_goff[C::kInstPerWave];
 #pragma unroll
   for (int i = 0; i < C::kInstPerWave; ++i) {
     const int r = (wave * C::kInstPerWave + i) * C::kRowsPerInst + lane / C::kChunks;
     const int pc = lane % C::kChunks;  // chunk position this lane fills
     const int kc = pc ^ (r & (C::kChunks - 1));
     const int vc = (((pc >> 1) ^ (r & (C::kChunks / 2 - 1))) << 1) | (pc & 1);
-    ld_row[i] = r;
     k_goff[i] = r * C::kRowBytes + kc * 16;
     v_goff[i] = r * C::kRowBytes + vc * 16;
   }
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
-  auto issue_tile = [&](const char* gbase, int kt, int stage_off, const int (&goff)[C::kInstPerWave]) {
-    const char* gt = gbase + (size_t)kt * C::kTileBytes;
-    const int valid = T - kt * kBN;  // rows of this tile that exist
-    if (valid >= kBN) {
+  const i32x4 k_buf = make_raw_buffer(Kb, (unsigned)T * C::kRowBytes);
+  const i32x4 v_buf = make_raw_buffer(Vb, (unsigned)T * C::kRowBytes);
+  // copy instruction i (of kInstPerWave) of this wave's share of tile kt
+  auto issue_one = [&](const i32x4& buf, int kt, int stage_off, const int (&goff)[C::kInstPerWave], int i) {
+    copy16_to_lds(buf, goff[i], kt * C::kTileBytes,
+                  smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
+  };
+  auto issue_tile = [&](const i32x4& buf, int kt, int stage_off, const int (&goff)[C::kInstPerWave]) {
 #pragma unroll
-      for (int i = 0; i < C::kInstPerWave; ++i)
-        copy16_to_lds(gt, goff[i], smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
-    } else {
-      // ragged last tile: rows past the end re-read the last row (their keys are masked later)
-#pragma unroll
-      for (int i = 0; i < C::kInstPerWave; ++i) {
-        const int r = min(ld_row[i], valid - 1);
-        copy16_to_lds(gt, goff[i] + (r - ld_row[i]) * C::kRowBytes,
-                      smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
-      }
-    }
+    for (int i = 0; i < C::kInstPerWave; ++i) issue_one(buf, kt, stage_off, goff, i);
   };
   auto k_stage_off = [&](int kt) { return (kt % kStagesK) * C::kTileBytes; };
   auto v_stage_off = [&](int kt) { return C::kVBase + ((kt + kStagesV) % kStagesV) * C::kTileBytes; };
@@ -402,8 +420,8 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
 
   // ---- prologue: fill the rings, zero the V stage that stands in for "tile -1"
   // (its P is zero too, but 0 * garbage could be NaN), S(0) = K(0) Q^T.
-  for (int j = 0; j < kStagesK && j < nt; ++j) issue_tile(Kb, j, k_stage_off(j), k_goff);
-  for (int j = 0; j < kStagesV - 1 && j < nt; ++j) issue_tile(Vb, j, v_stage_off(j), v_goff);
+  for (int j = 0; j < kStagesK; ++j) issue_tile(k_buf, j, k_stage_off(j), k_goff);
+  for (int j = 0; j < kStagesV - 1; ++j) issue_tile(v_buf, j, v_stage_off(j), v_goff);
   for (int i = tid * 16; i < C::kTileBytes; i += kThreads * 16)
     *(i32x4*)(smem + v_stage_off(-1) + i) = (i32x4){0, 0, 0, 0};
   wait_copies_but<0>();
@@ -420,17 +438,13 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   Pre3 kpre, vpre;
   {
     const unsigned char* ks0 = smem + k_stage_off(0);
-    kpre.f[0] = read_kfrag<D, 0>(ks0, fb);
-    kpre.f[1] = read_kfrag<D, 1>(ks0, fb);
-    kpre.f[2] = read_kfrag<D, 2>(ks0, fb);
+    static_for<kAhead>([&](auto I) { kpre.f[decltype(I)::value] = read_kfrag<D, decltype(I)::value>(ks0, fb); });
     qk_phase<D, false>(sA, ks0, kpre, qf, sA, pA, zero2, l_run, c2, fb);
     MODA_PIN();
     MODA_NOP(15);
     if (wave_last == 0 && needs_mask(0)) mask_tile(sA, 0);
     const unsigned char* vs = smem + v_stage_off(-1);
-    vpre.f[0] = read_vfrag<D, 0>(vs, fb);
-    vpre.f[1] = read_vfrag<D, 1>(vs, fb);
-    vpre.f[2] = read_vfrag<D, 2>(vs, fb);
+    static_for<kAhead>([&](auto I) { vpre.f[decltype(I)::value] = read_vfrag<D, decltype(I)::value>(vs, fb); });
   }
 
   // ---- steady state.  Step kt (scores of tile kt are in `cur`, P of tile kt-1 in `pprev`):
@@ -449,9 +463,8 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     if (kt <= wave_last) {
       const unsigned char* vs = smem + v_stage_off(kt - 1);
       i32x4 vf[NFV];
-      vf[0] = vpre.f[0];
-      vf[1] = vpre.f[1];
-      vf[2] = vpre.f[2];
+      #pragma unroll
+      for (int i = 0; i < kAhead; ++i) vf[i] = vpre.f[i];
       pv_phase<D, 0, HEAD, 1>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
       const bool raise = (mx[0] - m_run[0]) * c2 > 8.f || (mx[1] - m_run[1]) * c2 > 8.f;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) {
@@ -482,16 +495,13 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       // (for this wave's last tile the next K tile is not needed; it is read and
       //  multiplied all the same, which keeps the loop body free of branches)
       const unsigned char* ksn = smem + k_stage_off(kt + 1);
-      kpre.f[0] = read_kfrag<D, 0>(ksn, fb);
-      kpre.f[1] = read_kfrag<D, 1>(ksn, fb);
-      kpre.f[2] = read_kfrag<D, 2>(ksn, fb);
+      static_for<kAhead>([&](auto I) { kpre.f[decltype(I)::value] = read_kfrag<D, decltype(I)::value>(ksn, fb); });
     } else if (kt == wave_last + 1) {
       // this wave's last tile: only its P V is left
       const unsigned char* vs = smem + v_stage_off(kt - 1);
       i32x4 vf[NFV];
-      vf[0] = vpre.f[0];
-      vf[1] = vpre.f[1];
-      vf[2] = vpre.f[2];
+      #pragma unroll
+      for (int i = 0; i < kAhead; ++i) vf[i] = vpre.f[i];
       pv_phase<D, 0, NFV, 0>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
       clear(kpre);
       clear(pcur);
@@ -500,32 +510,41 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       clear(pcur);
     }
 
+    // Every step issues the same number of copies (tiles past the end of the tensor are
+    // out of range of the raw buffer: nothing is fetched), so "all but the newest
+    // 2*kInstPerWave copies have landed" always means: K tile kt+2 and V tile kt, which
+    // are read next, are complete.
+    const int kt_k = kt + kStagesK, kt_v = kt + kStagesV - 1;
+    const int so_k = k_stage_off(kt_k), so_v = v_stage_off(kt_v);
     if (kt < nt) {
-      // The copies issued at the previous step (K tile kt+3, V tile kt+1) may still be in
-      // flight; everything older must have landed: K tile kt+2 and V tile kt are read next.
-      const int newer = ((kt + kStagesK - 1 < nt) ? C::kInstPerWave : 0) +
-                        ((kt >= 1 && kt + kStagesV - 2 < nt) ? C::kInstPerWave : 0);
-      if (newer == 2 * C::kInstPerWave) wait_copies_but<2 * C::kInstPerWave>();
-      else if (newer == C::kInstPerWave) wait_copies_but<C::kInstPerWave>();
-      else wait_copies_but<0>();
+      wait_copies_but<2 * C::kInstPerWave>();
       __syncthreads();
       // every wave is past the first half of step kt: K tile kt and V tile kt-1 are dead
-      if (kt + kStagesK < nt) issue_tile(Kb, kt + kStagesK, k_stage_off(kt + kStagesK), k_goff);
-      if (kt + kStagesV - 1 < nt) issue_tile(Vb, kt + kStagesV - 1, v_stage_off(kt + kStagesV - 1), v_goff);
+      if (kt > wave_last) {
+        issue_tile(k_buf, kt_k, so_k, k_goff);
+        issue_tile(v_buf, kt_v, so_v, v_goff);
+      }
     }
 
     if (kt <= wave_last) {
       const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
-      qk_phase<D, true>(nxt, smem + k_stage_off(kt + 1), kpre, qf, cur, pcur, mc, l_run, c2, fb);
+      // this step's copies ride along, one after every fourth MFMA
+      auto hook = [&](auto M) {
+        constexpr int m = decltype(M)::value;
+        if constexpr (m % 4 == 1 && m / 4 < 2 * C::kInstPerWave) {
+          constexpr int i = m / 4;
+          if constexpr (i < C::kInstPerWave) issue_one(k_buf, kt_k, so_k, k_goff, i);
+          else issue_one(v_buf, kt_v, so_v, v_goff, i - C::kInstPerWave);
+        }
+      };
+      qk_phase<D, true>(nxt, smem + k_stage_off(kt + 1), kpre, qf, cur, pcur, mc, l_run, c2, fb, hook);
       if (kt + 1 == wave_last && needs_mask(kt + 1)) {
         MODA_PIN();
         MODA_NOP(15);
         mask_tile(nxt, kt + 1);
       }
       const unsigned char* vs = smem + v_stage_off(kt);
-      vpre.f[0] = read_vfrag<D, 0>(vs, fb);
-      vpre.f[1] = read_vfrag<D, 1>(vs, fb);
-      vpre.f[2] = read_vfrag<D, 2>(vs, fb);
+      static_for<kAhead>([&](auto I) { vpre.f[decltype(I)::value] = read_vfrag<D, decltype(I)::value>(vs, fb); });
     } else {
       clear(nxt);
       clear(vpre);
@@ -536,7 +555,8 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     if (kt + 1 <= nt) step(kt + 1, sB, sA, pB, pA);
   }
   MODA_PIN();
-  MODA_NOP(15);  // accumulators final before they are read out
+  MODA_NOP(15);          // accumulators final before they are read out
+  wait_copies_but<0>();  // the ring is reused below: no copy may still be landing in it
   __syncthreads();
 
   // ================= epilogue: accumulator layout -> row-major, depth slots, store
@@ -553,13 +573,14 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   char* Ob = (char*)p.O + (size_t)bh * T * C::kRowBytes;
   float* LSEb = p.LSE + (size_t)bh * T;
 
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    float l_tot = pair_sum(l_run[nb]);
+  // accumulators of query block NB -> this wave's exchange buffer, (m, l) per row
+  auto exchange = [&](auto NB) {
+    constexpr int nb = decltype(NB)::value;
+    const float l_tot = pair_sum(l_run[nb]);
     static_for<C::kDBlocks>([&](auto DBI) {
       constexpr int db = decltype(DBI)::value;
       float x[16];
-      if (nb == 0) read_o<db * 2>(x); else read_o<db * 2 + 1>(x);
+      read_o<db * 2 + nb>(x);
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         f32x4 v = {x[4 * bq], x[4 * bq + 1], x[4 * bq + 2], x[4 * bq + 3]};
@@ -573,71 +594,160 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  // row state in the row-major mapping
+  float o[8], m = 0.f, l = 1.f;
+  auto load_row = [&](int row) {
+    const f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
+    const f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
+    o[0] = o0[0]; o[1] = o0[1]; o[2] = o0[2]; o[3] = o0[3];
+    o[4] = o1[0]; o[5] = o1[1]; o[6] = o1[2]; o[7] = o1[3];
+    m = ml[2 * row];
+    l = ml[2 * row + 1];
+  };
+  auto store_row = [&](int t) {
+    if (t < T) {
+      const float inv = 1.0f / l;
+      u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
+                  pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
+      *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
+      if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
+    }
+  };
+  constexpr int NIT = 32 / RPS;  // row steps per query block
 
-    for (int it = 0; it < 32 / RPS; ++it) {
-      const int row = it * RPS + rg;
-      const int t = qw0 + nb * 32 + row;
-      const int tc = min(t, T - 1);  // rows past the end compute on row T-1 and are not stored
-      f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
-      f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
-      float o[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
-      float m = ml[2 * row];
-      float l = ml[2 * row + 1];
-      if (L > 0) {
-        const u32x4 qv = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
-        const char* kd = Kdb + (size_t)tc * drow + l16 * 16;
-        const char* vd = Vdb + (size_t)tc * drow + l16 * 16;
-        for (int i0 = 0; i0 < L; i0 += kDepthChunk) {
-          // All loads of the chunk are issued before anything waits on them; slots
-          // past depth_count re-read the last valid slot and get weight zero.
-          u32x4 kv[kDepthChunk], vv[kDepthChunk];
-#pragma unroll
-          for (int i = 0; i < kDepthChunk; ++i)
-            kv[i] = *(const u32x4*)(kd + (size_t)min(i0 + i, L - 1) * C::kRowBytes);
-#pragma unroll
-          for (int i = 0; i < kDepthChunk; ++i)
-            vv[i] = *(const u32x4*)(vd + (size_t)min(i0 + i, L - 1) * C::kRowBytes);
-          float sc[kDepthChunk];
-          float mx = m;
-#pragma unroll
-          for (int i = 0; i < kDepthChunk; ++i) {
-            float a = dot2_bf16(qv[0], kv[i][0], 0.f);
-            a = dot2_bf16(qv[1], kv[i][1], a);
-            a = dot2_bf16(qv[2], kv[i][2], a);
-            a = dot2_bf16(qv[3], kv[i][3], a);
-            a = group_sum<LPR>(a);
-            sc[i] = (i0 + i < L) ? a : -INFINITY;
-            mx = fmaxf(mx, sc[i]);
-          }
-          const float al = fast_exp2((m - mx) * c2);
-          const float mc = mx * c2;
-          m = mx;
-          l *= al;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) o[k] *= al;
-#pragma unroll
-          for (int i = 0; i < kDepthChunk; ++i) {
-            const float pw = fast_exp2(sc[i] * c2 - mc);
-            l += pw;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              o[2 * k] += pw * bf16_lo(vv[i][k]);
-              o[2 * k + 1] += pw * bf16_hi(vv[i][k]);
-            }
-          }
-        }
+  if (L == 0) {
+    static_for<2>([&](auto NB) {
+      constexpr int nb = decltype(NB)::value;
+      exchange(NB);
+      for (int it = 0; it < NIT; ++it) {
+        const int row = it * RPS + rg;
+        load_row(row);
+        store_row(qw0 + nb * 32 + row);
       }
-      if (t < T) {
-        const float inv = 1.0f / l;
-        u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
-                    pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
-        *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
-        if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    });
+    return;
+  }
+
+  // ---- depth slots.  Work items (query block, row step, chunk of kDepthChunk slots) are
+  // walked in order with the NEXT item's loads already in flight while the current
+  // item is folded into the row's (m, l, o): the phase is bound by memory latency, so
+  // the loads of one item must never wait for the arithmetic of another.
+  struct DepthBuf {
+    u32x4 q;
+    u32x4 k[kDepthChunk], v[kDepthChunk];
+  };
+  const int nch = (L + kDepthChunk - 1) / kDepthChunk;
+  // The depth slabs are read through bounds-checked raw buffers with 32-bit offsets:
+  // a chunk's slots past depth_alloc at the very end of the slab read as zero, and no
+  // index clamping is needed (slots past depth_count get weight zero below).
+  const size_t slab_bytes = (size_t)T * drow;
+  const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)Vdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
+  auto issue = [&](int nb, int it, int c, DepthBuf& buf) {
+    const int tc = min(qw0 + nb * 32 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
+    buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
+    const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+    const int soff = c * kDepthChunk * C::kRowBytes;
+#pragma unroll
+    for (int i = 0; i < kDepthChunk; ++i)
+      buf.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+#pragma unroll
+    for (int i = 0; i < kDepthChunk; ++i)
+      buf.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+  };
+  auto fold = [&](int c, const DepthBuf& buf) {
+    float sc[kDepthChunk];
+    float mx = m;
+#pragma unroll
+    for (int i = 0; i < kDepthChunk; ++i) {
+      float a = dot2_bf16(buf.q[0], buf.k[i][0], 0.f);
+      a = dot2_bf16(buf.q[1], buf.k[i][1], a);
+      a = dot2_bf16(buf.q[2], buf.k[i][2], a);
+      a = dot2_bf16(buf.q[3], buf.k[i][3], a);
+      a = group_sum<LPR>(a);
+      sc[i] = (c * kDepthChunk + i < L) ? a : -INFINITY;
+      mx = fmaxf(mx, sc[i]);
+    }
+    const float al = fast_exp2((m - mx) * c2);
+    const float mc = mx * c2;
+    m = mx;
+    l *= al;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] *= al;
+#pragma unroll
+    for (int i = 0; i < kDepthChunk; ++i) {
+      const float pw = fast_exp2(sc[i] * c2 - mc);
+      l += pw;
+      // weight rounded to bf16 (as P is for the sequence keys) and placed in the low or
+      // the high half of a pair: one packed dot product per output channel
+      const uint32_t w_lo = pack_bf16(pw, 0.f);
+      const uint32_t w_hi = w_lo << 16;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        o[2 * k] = dot2_bf16(w_lo, buf.v[i][k], o[2 * k]);
+        o[2 * k + 1] = dot2_bf16(w_hi, buf.v[i][k], o[2 * k + 1]);
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  // Item cursors: (nb, it, c) is the item being folded, (nbi, iti, ci) the next one
+  // whose loads are to be issued (two items ahead).  Past the end the issue cursor
+  // stays on the last item (its loads are repeated and ignored): a conditional issue
+  // would make the compiler wait for the older loads as if the newer ones were not there.
+  int nb = 0, it = 0, c = 0;
+  int nbi = 0, iti = 0, ci = 0;
+  auto advance = [&](int& b_, int& i_, int& c_) {
+    if (++c_ == nch) {
+      c_ = 0;
+      if (++i_ == NIT) {
+        i_ = 0;
+        ++b_;
+      }
+    }
+  };
+  auto issue_next = [&](DepthBuf& buf) {
+    issue(nbi, iti, ci, buf);
+    int b2 = nbi, i2 = iti, c2n = ci;
+    advance(b2, i2, c2n);
+    if (b2 < 2) {
+      nbi = b2;
+      iti = i2;
+      ci = c2n;
+    }
+    MODA_PIN();  // these loads are issued before anything below waits for older ones
+  };
+  // fold the current item from `cur`; false when it was the last one
+  auto one = [&](const DepthBuf& cur, DepthBuf& refill) -> bool {
+    issue_next(refill);
+    if (it == 0 && c == 0) {
+      if (nb == 0) {
+        exchange(std::integral_constant<int, 0>{});
+      } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        exchange(std::integral_constant<int, 1>{});
+      }
+    }
+    const int row = it * RPS + rg;
+    if (c == 0) load_row(row);
+    fold(c, cur);
+    if (c == nch - 1) store_row(qw0 + nb * 32 + row);
+    advance(nb, it, c);
+    return nb < 2;
+  };
+  DepthBuf bufA, bufB, bufC;
+  issue_next(bufA);
+  issue_next(bufB);
+  while (true) {
+    if (!one(bufA, bufC)) break;
+    if (!one(bufB, bufA)) break;
+    if (!one(bufC, bufB)) break;
   }
 }
 
