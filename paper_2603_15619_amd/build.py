@@ -28,11 +28,12 @@ def _compile(src):
     return obj
 
 
-# Sources whose inline assembly owns accumulation registers a128..a255 by name (see
-# csrc/gen_acc_regs.py).  The compiler is not told that they hold live values, so the
-# build verifies on the generated assembly that it never touches them itself.
+# Sources whose inline assembly owns ALL accumulation registers by name (see
+# csrc/moda_fwd_regs.h).  The compiler is not told that they hold live values, so the
+# build verifies on the generated assembly that it never touches one itself, and that
+# nothing was spilled to scratch memory.
 NAMED_ACC_SOURCES = ("moda_fwd_bf16.hip",)
-FIRST_NAMED_ACC = 128
+FIRST_NAMED_ACC = 0
 
 
 def check_named_acc_registers(src) -> None:
@@ -58,6 +59,8 @@ def check_named_acc_registers(src) -> None:
             if hi >= FIRST_NAMED_ACC:
                 raise RuntimeError("%s:%d: compiler-allocated use of a%d collides with the named "
                                    "accumulation registers: %s" % (asm, n, hi, line.strip()))
+        if code.strip().startswith(("scratch_", "buffer_store", "buffer_load")) and "off" in code and "s[0:3]" in code:
+            raise RuntimeError("%s:%d: register spill to scratch memory: %s" % (asm, n, line.strip()))
 
 
 def build_libmoda() -> str:

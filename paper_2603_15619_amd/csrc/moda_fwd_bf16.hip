@@ -1,19 +1,25 @@
 // MoDA attention forward, bf16 inputs, fp32 online-softmax state, gfx950 MFMA.
 //
-// One workgroup = 4 waves = one tile of 256 queries of one (b, h); each wave owns
-// 64 queries.  Sequence K/V tiles of 64 keys are copied global -> LDS without
-// passing through registers, into rings of 4 (K) and 3 (V) stages, two iterations
-// ahead of their use, and consumed by v_mfma_f32_32x32x16_bf16:
+// One workgroup = 8 waves (two per SIMD) = one tile of 256 queries of one (b, h); each
+// wave owns 32 queries.  Two waves per SIMD matter: a single wave issues a vector-ALU
+// instruction only every ~8 cycles and an exp2 every ~24, two waves together reach
+// ~5.7 and ~9.4 (measured), and the softmax arithmetic of this operator needs about as
+// many vector-ALU cycles as its matrix products need matrix-pipe cycles.
+// Sequence K/V tiles of 64 keys are copied global -> LDS without passing through
+// registers, into rings of 4 stages each, two iterations ahead of their use, and
+// consumed by v_mfma_f32_32x32x16_bf16:
 //   S^T = K Q^T   (keys on the MFMA M axis, queries on N): a lane then holds 16
 //                 scores of ONE query per 32x32 block, so the row max / row sum
 //                 are in-lane reductions plus one exchange with lane ^ 32;
 //   O^T += V^T P^T with P^T taken straight from the S^T accumulators (no layout
 //                 round trip); the V^T operand comes from ds_read_b64_tr_b16.
-// The key loop is software pipelined so that the matrix pipe never waits for the
-// vector ALUs: while tile kt-1's P V and tile kt+1's K Q^T run on the matrix pipe,
-// the vector ALUs take the row max of tile kt and exponentiate it, a fixed slice
-// after every MFMA.  The output accumulators and the resident Q fragments sit in
-// named accumulation registers (moda_acc_regs.inc), score tiles in vector registers.
+// The key loop is software pipelined: while tile kt-1's P V and tile kt+1's K Q^T run
+// on the matrix pipe, the vector ALUs take the row max of tile kt and exponentiate it,
+// a fixed slice after every MFMA.  The loop body is unrolled over the 4 ring stages, so
+// every LDS address is a per-lane base register plus an immediate.  K / V^T fragments
+// are read from LDS straight into named accumulation registers a fixed number of MFMAs
+// ahead of their use (moda_fwd_regs.h), next to the Q fragments and the output
+// accumulators; score tiles, P and the softmax state live in the 128 vector registers.
 // Tiles above the diagonal are never loaded; only the diagonal tile is masked
 // (Algorithm 1's split into fully visible and boundary blocks).
 // After the sequence loop the accumulators pass through LDS into a row-major
@@ -26,25 +32,22 @@
 #include <utility>
 
 #include "moda_launch.h"
-
-namespace moda {
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-}
-#include "moda_acc_regs.inc"
+#include "moda_fwd_regs.h"
 
 namespace moda {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kQPerWave = 64;
+constexpr int kQPerWave = 32;            // one 32-query MFMA block per wave
 constexpr int kBM = kWaves * kQPerWave;  // 256 queries per workgroup
 constexpr int kBN = 64;                  // keys per LDS tile
-constexpr int kStagesK = 4;              // LDS ring depth for K tiles
-constexpr int kStagesV = 3;              // LDS ring depth for V tiles
+constexpr int kStages = 4;               // LDS ring depth, K and V each; the key loop is unrolled by it
 // cache policy of loads whose data is used exactly once (depth K/V): non-temporal, so
 // that the stream does not push the re-used sequence K/V tiles out of the L2
 constexpr int kStreamOnce = 2;
-constexpr int kDepthChunk = 8;           // depth slots per work item of the depth phase
+constexpr int kDepthChunk = 5;           // depth slots per work item of the depth phase
+constexpr int kAhead = 4;                // fragments read from LDS ahead of the MFMA that consumes them
+static_assert(kAhead < kSlots - 1, "a slot is refilled only after the MFMA that read it was issued");
 
 template <int D>
 struct FwdCfg {
@@ -53,15 +56,19 @@ struct FwdCfg {
   static constexpr int kTileBytes = kBN * kRowBytes;
   static constexpr int kDSteps = D / 16;         // MFMA k-steps over the head dim
   static constexpr int kDBlocks = D / 32;        // 32-wide output blocks over the head dim
+  static constexpr int kNFK = kDSteps * 2;       // K fragments (= MFMAs of S^T = K Q^T) per tile
+  static constexpr int kNFV = 4 * kDBlocks;      // V^T fragments (= MFMAs of O^T += V^T P^T) per tile
+  static_assert(kNFK % kSlots == 0 && kNFV % kSlots == 0, "fragment f always uses slot f % kSlots");
   // fp32 exchange buffer: 32 query rows x D floats per wave, rows padded by 16 B
   static constexpr int kXRow = D * 4 + 16;
   static constexpr int kXWave = 32 * kXRow + 32 * 8;  // + (m, l) per row
   static constexpr int kXBytes = kWaves * kXWave;
-  static constexpr int kVBase = kStagesK * kTileBytes;  // V ring follows the K ring
-  static constexpr int kRingBytes = (kStagesK + kStagesV) * kTileBytes;
+  static constexpr int kVBase = kStages * kTileBytes;  // V ring follows the K ring
+  static constexpr int kRingBytes = 2 * kStages * kTileBytes;
   static constexpr int kLds = kRingBytes > kXBytes ? kRingBytes : kXBytes;
   static constexpr int kRowsPerInst = 64 / kChunks;                 // tile rows per wave copy instruction
   static constexpr int kInstPerWave = kBN / kRowsPerInst / kWaves;  // copy instructions per wave per tile
+  static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
 };
 
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
@@ -84,6 +91,14 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 #define MODA_ANCHOR(x) asm volatile("" : "+v"(x))
 // n+1 idle issue slots (n <= 15)
 #define MODA_NOP(n) asm volatile("s_nop " #n ::: "memory")
+
+// Lane index within the wave, recomputed where it is needed (2 instructions) instead of
+// being kept in a register across the key loop: volatile, so it is neither hoisted nor merged.
+__device__ __forceinline__ int lane_id() {
+  int x;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
+  return x;
+}
 
 // 16 bytes per lane, global -> LDS, no register staging: lane i's bytes land at
 // lds_addr + 16 i.  The source is a raw buffer (base, size in bytes): lanes whose
@@ -122,112 +137,109 @@ __device__ __forceinline__ void wait_copies_but() {  // all but the N most recen
 //           conflict free.
 //   V tile: the 32-byte pair (c >> 1) sits at pair position (c >> 1) ^ (r & (chunks/2-1));
 //           the transposing read (16 lanes read 4 rows x 32 B) is then conflict free.
-// Every fragment address below is (per-lane base ^ constant) + stage offset + constant;
-// the last constant rides in the instructions' immediate offset.
+// Every fragment address is (per-lane base ^ constant), kept in a register, plus
+// stage offset + constant in the instruction's immediate.
 template <int D>
 struct FragBase {
-  int k[FwdCfg<D>::kDSteps];   // K: lane base ^ (st << 5)
-  int v[FwdCfg<D>::kDBlocks];  // V: lane base ^ (db << 6)
-  __device__ __forceinline__ void init(int lane) {
+  int k[FwdCfg<D>::kDSteps];   // K ring: lane base ^ (st << 5)
+  int v[FwdCfg<D>::kDBlocks];  // V ring: (lane base ^ (db << 6)) + offset of the V ring
+  __device__ __forceinline__ void init(int lane, int smem_addr) {
     using C = FwdCfg<D>;
     const int l32 = lane & 31, hi = lane >> 5;
     // K fragment (st, kb): row kb*32 + l32, logical chunk 2*st + hi
     const int kbase = l32 * C::kRowBytes + (((l32 & (C::kChunks - 1)) ^ hi) << 4);
 #pragma unroll
-    for (int st = 0; st < C::kDSteps; ++st) k[st] = kbase ^ (st << 5);
+    for (int st = 0; st < C::kDSteps; ++st) k[st] = smem_addr + (kbase ^ (st << 5));
     // V fragment (ks, db): transposing read, see read_vfrag
     const int r8 = hi * 4 + ((lane & 15) >> 2);  // row inside the 16-key group (first read)
     const int grp = (lane >> 4) & 1;             // which 16 channels of the 32-channel block
     const int x = r8 & (C::kChunks / 2 - 1);
     const int vbase = r8 * C::kRowBytes + ((grp ^ x) << 5) + (lane & 3) * 8;
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db) v[db] = vbase ^ (db << 6);
+    for (int db = 0; db < C::kDBlocks; ++db) v[db] = smem_addr + C::kVBase + (vbase ^ (db << 6));
   }
 };
 
-// K fragment IDX = st*2 + kb: 32 keys x 16 channels; this lane reads 8 channels of one key.
-// `stage` = smem + byte offset of the ring stage.
-template <int D, int IDX>
-__device__ __forceinline__ i32x4 read_kfrag(const unsigned char* stage, const FragBase<D>& fb) {
-  constexpr int st = IDX >> 1, kb = IDX & 1;
-  return *(const i32x4*)(stage + fb.k[st] + kb * 32 * FwdCfg<D>::kRowBytes);
+// K fragment F = st*2 + kb of the tile in ring stage KS: 32 keys x 16 channels; this
+// lane reads 8 channels of one key.
+template <int D, int KS, int F>
+__device__ __forceinline__ void read_kfrag(const FragBase<D>& fb) {
+  using C = FwdCfg<D>;
+  constexpr int st = F >> 1, kb = F & 1;
+  read_k_slot<F % kSlots, KS * C::kTileBytes + kb * 32 * C::kRowBytes>(fb.k[st]);
 }
-
-// V^T fragment F = ks*kDBlocks + db of a 64-key tile: 16 keys x 32 channels.
+// V^T fragment F = ks*kDBlocks + db of the tile in ring stage VS: 16 keys x 32 channels.
 // Transposing read: within 16 lanes, lane i supplies row (i/4), 8-byte piece (i%4)
 // of a 4-key x 16-channel block and receives channel i of the 4 keys.  MFMA k-slots
 // 0..7 (lanes < 32) are keys {0..3, 8..11} of the 16-key group and slots 8..15
 // (lanes >= 32) keys {4..7, 12..15}: how the S^T accumulators hold P^T.
-template <int D, int F>
-__device__ __forceinline__ i32x4 read_vfrag(const unsigned char* stage, const FragBase<D>& fb) {
-  constexpr int DB = FwdCfg<D>::kDBlocks;
-  constexpr int ks = F / DB, db = F % DB;
-  const unsigned char* a0 = stage + fb.v[db] + ks * 16 * FwdCfg<D>::kRowBytes;
-  const unsigned char* a1 = a0 + 8 * FwdCfg<D>::kRowBytes;
-  s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
-  s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a1);
-  s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(i32x4, v01);
+template <int D, int VS, int F>
+__device__ __forceinline__ void read_vfrag(const FragBase<D>& fb) {
+  using C = FwdCfg<D>;
+  constexpr int ks = F / C::kDBlocks, db = F % C::kDBlocks;
+  read_v_slot<F % kSlots, VS * C::kTileBytes + ks * 16 * C::kRowBytes, 8 * C::kRowBytes>(fb.v[db]);
 }
 
-// One wave's share of a 64-key x 64-query score tile (vector registers).
+// One wave's share of a 64-key x 32-query score tile (vector registers).
 struct STile {
-  f32x16 a[2][2];  // [key block of 32][query block of 32]
+  f32x16 a[2];  // [key block of 32]
 };
 // P^T (packed bf16) of one tile as MFMA B operands.
 struct PTile {
-  i32x4 a[2][2][2];  // [key block of 32][16-key half][query block]
-};
-// The first fragments of the next matrix phase, read ahead of it.
-constexpr int kAhead = 4;  // fragments read ahead of the MFMA that consumes them
-struct Pre3 {
-  i32x4 f[kAhead];
+  i32x4 a[2][2];  // [key block of 32][16-key half]
 };
 
-// Values that are not produced on some control path are set to zero there, so that
-// the compiler does not have to keep their stale contents alive.
-__device__ __forceinline__ void clear(STile& s) {
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s.a[kb][nb][i] = 0.f;
-}
+// Values that are not produced on some control path are declared overwritten there
+// (with unspecified contents that nothing reads), so that the compiler does not have
+// to keep their stale contents alive.
+__device__ __forceinline__ void clear(STile& s) { asm volatile("" : "=v"(s.a[0]), "=v"(s.a[1])); }
 __device__ __forceinline__ void clear(PTile& t) {
+  asm volatile("" : "=v"(t.a[0][0]), "=v"(t.a[0][1]), "=v"(t.a[1][0]), "=v"(t.a[1][1]));
+}
+// All-zero P (multiplied with the zero-filled V stage that stands in for "tile -1").
+__device__ __forceinline__ void zero(PTile& t) {
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) t.a[kb][hf][nb] = (i32x4){0, 0, 0, 0};
-}
-__device__ __forceinline__ void clear(Pre3& t) {
-#pragma unroll
-  for (int i = 0; i < kAhead; ++i) t.f[i] = (i32x4){0, 0, 0, 0};
+      for (int i = 0; i < 4; ++i) asm volatile("v_mov_b32 %0, 0" : "=v"(t.a[kb][hf][i]));
 }
 
-// exp2 of two adjacent scores: pair Q of a tile, Q = kb*16 + nb*8 + j.
+// exp2 of two adjacent scores: pair Q of a tile, Q = kb*8 + j.
 template <int Q>
-__device__ __forceinline__ void exp_pair(const STile& s, PTile& pt, const float (&mc)[2],
-                                         float (&l_run)[2], float c2) {
-  constexpr int kb = Q >> 4, nb = (Q >> 3) & 1, j = Q & 7;
-  const float e0 = fast_exp2(s.a[kb][nb][2 * j] * c2 - mc[nb]);
-  const float e1 = fast_exp2(s.a[kb][nb][2 * j + 1] * c2 - mc[nb]);
-  float l = l_run[nb] + (e0 + e1);
+__device__ __forceinline__ void exp_pair(const STile& s, PTile& pt, float mc, float& l_run, float c2) {
+  constexpr int kb = Q / 8, j = Q % 8;
+  const float e0 = fast_exp2(s.a[kb][2 * j] * c2 - mc);
+  const float e1 = fast_exp2(s.a[kb][2 * j + 1] * c2 - mc);
+  float l = l_run + (e0 + e1);
   int pk = (int)pack_bf16(e0, e1);
   MODA_ANCHOR(l);
   MODA_ANCHOR(pk);
-  l_run[nb] = l;
-  pt.a[kb][j >> 2][nb][j & 3] = pk;
+  l_run = l;
+  pt.a[kb][j >> 2][j & 3] = pk;
 }
 
-// ---- matrix phase 1: S^T(next) = K Q^T over one 64-key tile (4*kDSteps MFMAs), with
-// exp2 of the CURRENT tile's second key block (pairs 16..31) spread between the MFMAs
-// when WITH_EXP.  `pre` holds K fragments 0..2, read before the call.  The hardware
-// does not interlock a matrix result against a vector-ALU reader: the caller keeps
-// at least 12 issue slots between the end of this function and the first read of
-// `nxt` (an MFMA of the next phase counts 8).
+// The LDS reads form one stream per wave: V^T fragments 0..NFV-1 of a tile, then K
+// fragments 0..NFK-1 of the next score tile, then V^T fragments again, ...; the read
+// of the fragment kAhead places further on is issued just before each MFMA, and every
+// fragment lands in slot (its index % kSlots).  LDS operations issued after the read of
+// the fragment that MFMA number F of a phase consumes (kAhead fragments, of 1 or 2
+// reads each):
+template <int F, int NF, int OPS_THIS, int OPS_NEXT>
+constexpr int ops_after() {
+  int n = 0;
+  for (int j = 1; j <= kAhead; ++j) n += (F + j < NF) ? OPS_THIS : OPS_NEXT;
+  return n;
+}
+
+// ---- matrix phase 1: S^T(next) = K Q^T over the 64-key tile in K stage KS (kNFK
+// MFMAs), with exp2 of the CURRENT tile's second key block (pairs 8..15) spread
+// between the MFMAs when WITH_EXP.  The first kAhead K fragments were requested by the
+// phase before; this one requests the first V^T fragments of stage VSN for the phase
+// after.  The hardware does not interlock a matrix result against a vector-ALU reader:
+// the caller keeps at least 12 issue slots between the end of this function and the
+// first read of `nxt` (an MFMA of the next phase counts 8).
 // `hook(integral_constant<m>)` runs after MFMA number m: the caller spreads its
 // global->LDS copy instructions there, one at a time, so that their issue time is
 // hidden behind matrix work as well.
@@ -235,94 +247,80 @@ struct NoHook {
   template <class I>
   __device__ __forceinline__ void operator()(I) const {}
 };
-template <int D, bool WITH_EXP, class Hook = NoHook>
-__device__ __forceinline__ void qk_phase(STile& nxt, const unsigned char* kstage, const Pre3& pre,
-                                         const i32x4 (&qf)[2][FwdCfg<D>::kDSteps], const STile& cur,
-                                         PTile& pcur, const float (&mc)[2], float (&l_run)[2],
-                                         float c2, const FragBase<D>& fb, Hook hook = Hook{}) {
-  constexpr int NF = FwdCfg<D>::kDSteps * 2;
-  constexpr int NM = NF * 2;
-  i32x4 kf[NF];
-#pragma unroll
-  for (int i = 0; i < kAhead; ++i) kf[i] = pre.f[i];
+template <int D, int KS, int VSN, bool WITH_EXP, class Hook = NoHook>
+__device__ __forceinline__ void qk_phase(STile& nxt, const STile& cur, PTile& pcur, float mc,
+                                         float& l_run, float c2, const FragBase<D>& fb,
+                                         Hook hook = Hook{}) {
+  constexpr int NF = FwdCfg<D>::kNFK;
   static_for<NF>([&](auto F) {
     constexpr int f = decltype(F)::value;
     constexpr int st = f >> 1, kb = f & 1;
-    if constexpr (f + kAhead < NF) kf[f + kAhead] = read_kfrag<D, (f + kAhead < NF ? f + kAhead : 0)>(kstage, fb);
-    static_for<2>([&](auto NB) {
-      constexpr int nb = decltype(NB)::value;
-      if constexpr (st == 0) mfma_s_init(nxt.a[kb][nb], kf[f], qf[nb][st]);
-      else mfma_s_acc(nxt.a[kb][nb], kf[f], qf[nb][st]);
-      if constexpr (WITH_EXP) {
-        constexpr int m = f * 2 + nb;
-        constexpr int lo = 16 + (m * 16) / NM, up = 16 + ((m + 1) * 16) / NM;
-        static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
-      }
-      hook(std::integral_constant<int, f * 2 + nb>{});
-      MODA_PIN();
-    });
+    constexpr int pf = f + kAhead;
+    if constexpr (pf < NF) read_kfrag<D, KS, (pf < NF ? pf : 0)>(fb);
+    else read_vfrag<D, VSN, (pf < NF ? 0 : pf - NF)>(fb);
+    lds_wait<ops_after<f, NF, 1, 2>()>();
+    mfma_s<f % kSlots, st, st == 0>(nxt.a[kb]);
+    if constexpr (WITH_EXP) {
+      constexpr int lo = 8 + (f * 8) / NF, up = 8 + ((f + 1) * 8) / NF;
+      static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
+    }
+    hook(F);
+    MODA_PIN();
   });
 }
 
-// ---- matrix phase 2: O^T += V^T P^T over one 64-key tile, V fragments FIRST..LAST-1
-// (2 MFMAs each).  MODE 0: nothing else.  MODE 1 (head, fragments of the first 16
-// keys): the row max of the current score tile is taken between the MFMAs, starting
-// after the second one (see qk_phase).  MODE 2 (tail): exp2 of the current tile's
-// first key block (pairs 0..15) is spread between the MFMAs.
-template <int D, int FIRST, int LAST, int MODE>
-__device__ __forceinline__ void pv_phase(const unsigned char* vstage, i32x4 (&vf)[4 * FwdCfg<D>::kDBlocks],
-                                         const PTile& pin, const STile& s, PTile& pout,
-                                         const float (&mc)[2], float (&l_run)[2], float (&mx)[2],
-                                         float c2, const FragBase<D>& fb) {
+// ---- matrix phase 2: O^T += V^T P^T over the 64-key tile in V stage VS, V^T fragments
+// FIRST..LAST-1 (one MFMA each); requests the first K fragments of stage KSN for the
+// phase after.  MODE 0: nothing else.  MODE 1 (head, fragments of the first 16 keys):
+// the row max of the current score tile is taken between the MFMAs, starting after the
+// second one (see qk_phase).  MODE 2 (tail): exp2 of the current tile's first key block
+// (pairs 0..7) is spread between the MFMAs.
+template <int D, int VS, int KSN, int FIRST, int LAST, int MODE>
+__device__ __forceinline__ void pv_phase(const PTile& pin, const STile& s, PTile& pout, float mc,
+                                         float& l_run, float& mx, float c2, const FragBase<D>& fb) {
   constexpr int DB = FwdCfg<D>::kDBlocks;
-  constexpr int NF = 4 * DB;
-  constexpr int NM = (LAST - FIRST) * 2;  // MFMAs in this call
-  float vmax[2][2];                        // MODE 1: partial maxima [nb][2 chains]
-  static_for<LAST - FIRST>([&](auto FI) {
-    constexpr int f = FIRST + decltype(FI)::value;
+  constexpr int NF = FwdCfg<D>::kNFV;
+  constexpr int NM = LAST - FIRST;  // MFMAs in this call
+  float vmax[2];                    // MODE 1: two independent chains of partial maxima
+  static_for<NM>([&](auto FI) {
+    constexpr int m = decltype(FI)::value;
+    constexpr int f = FIRST + m;
     constexpr int ks = f / DB, db = f % DB;
     constexpr int kb = ks >> 1, hf = ks & 1;
-    if constexpr (f + kAhead < NF) vf[f + kAhead] = read_vfrag<D, (f + kAhead < NF ? f + kAhead : 0)>(vstage, fb);
-    static_for<2>([&](auto NB) {
-      constexpr int nb = decltype(NB)::value;
-      mfma_o<db * 2 + nb>(vf[f], pin.a[kb][hf][nb]);
-      constexpr int m = (f - FIRST) * 2 + nb;  // MFMA index within this call
-      if constexpr (MODE == 1 && m >= 1) {
-        // 64 score registers (2 nb x 32) folded 3 at a time: 32 max3 steps spread over NM-1 slots
-        constexpr int lo = ((m - 1) * 32) / (NM - 1), up = (m * 32) / (NM - 1);
-        static_for<up - lo>([&](auto Z) {
-          constexpr int z = lo + decltype(Z)::value;      // step: nb2 = z / 16, within = z % 16
-          constexpr int nb2 = z >> 4, w = z & 15;         // step w folds registers 2w, 2w+1 of the 32
-          constexpr int kb2 = w >> 3, i0 = (w & 7) * 2;
-          constexpr int ch = w & 1;                        // two independent chains per nb
-          if constexpr (w < 2) vmax[nb2][ch] = fmaxf(s.a[kb2][nb2][i0], s.a[kb2][nb2][i0 + 1]);
-          else vmax[nb2][ch] = fmaxf(fmaxf(vmax[nb2][ch], s.a[kb2][nb2][i0]), s.a[kb2][nb2][i0 + 1]);
-          MODA_ANCHOR(vmax[nb2][ch]);
-        });
-      }
-      if constexpr (MODE == 2) {
-        constexpr int lo = (m * 16) / NM, up = ((m + 1) * 16) / NM;
-        static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(s, pout, mc, l_run, c2); });
-      }
-      MODA_PIN();
-    });
+    constexpr int pf = f + kAhead;
+    if constexpr (pf < NF) read_vfrag<D, VS, (pf < NF ? pf : 0)>(fb);
+    else read_kfrag<D, KSN, (pf < NF ? 0 : pf - NF)>(fb);
+    lds_wait<ops_after<f, NF, 2, 1>()>();
+    mfma_o<db, f % kSlots>(pin.a[kb][hf]);
+    if constexpr (MODE == 1 && m >= 1) {
+      // 32 score registers folded 2 at a time (v_max3): 16 steps spread over NM-1 slots
+      constexpr int lo = ((m - 1) * 16) / (NM - 1), up = (m * 16) / (NM - 1);
+      static_for<up - lo>([&](auto Z) {
+        constexpr int w = lo + decltype(Z)::value;  // step w folds registers 2w, 2w+1 of the 32
+        constexpr int kb2 = w >> 3, i0 = (w & 7) * 2;
+        constexpr int ch = w & 1;
+        if constexpr (w < 2) vmax[ch] = fmaxf(s.a[kb2][i0], s.a[kb2][i0 + 1]);
+        else vmax[ch] = fmaxf(fmaxf(vmax[ch], s.a[kb2][i0]), s.a[kb2][i0 + 1]);
+        MODA_ANCHOR(vmax[ch]);
+      });
+    }
+    if constexpr (MODE == 2) {
+      constexpr int lo = (m * 8) / NM, up = ((m + 1) * 8) / NM;
+      static_for<up - lo>([&](auto Q) { exp_pair<lo + decltype(Q)::value>(s, pout, mc, l_run, c2); });
+    }
+    MODA_PIN();
   });
-  if constexpr (MODE == 1) {
-    mx[0] = pair_max(fmaxf(vmax[0][0], vmax[0][1]));
-    mx[1] = pair_max(fmaxf(vmax[1][0], vmax[1][1]));
-  }
+  if constexpr (MODE == 1) mx = pair_max(fmaxf(vmax[0], vmax[1]));
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p) {
+__global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   using C = FwdCfg<D>;
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
+  reserve_acc_registers();
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31;
-  const int hi = lane >> 5;
 
   // Heavy (late) query tiles first; consecutive workgroup ids walk over (b, h)
   // so that, with ids dealt round-robin to the 8 XCDs, one XCD keeps serving
@@ -342,26 +340,20 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   const char* Vb = (const char*)p.Vseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
 
   // ---- Q fragments (MFMA B operand of S^T = K Q^T), resident in accumulation registers
-  i32x4 qf[2][C::kDSteps];
   {
-    i32x4 qtmp[2][C::kDSteps];  // all loads are issued before the first one is consumed
+    i32x4 qtmp[C::kDSteps];  // all loads are issued before the first one is consumed
+    const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
+    const int row = min(qw0 + l32, T - 1);
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int row = min(qw0 + nb * 32 + l32, T - 1);
-#pragma unroll
-      for (int st = 0; st < C::kDSteps; ++st)
-        qtmp[nb][st] = *(const i32x4*)(Qb + (size_t)row * C::kRowBytes + st * 32 + hi * 16);
-    }
+    for (int st = 0; st < C::kDSteps; ++st)
+      qtmp[st] = *(const i32x4*)(Qb + (size_t)row * C::kRowBytes + st * 32 + hi * 16);
     MODA_PIN();
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int st = 0; st < C::kDSteps; ++st) qf[nb][st] = to_acc(qtmp[nb][st]);
+    static_for<C::kDSteps>([&](auto ST) { set_q<decltype(ST)::value>(qtmp[decltype(ST)::value]); });
   }
-  static_for<C::kDBlocks * 2>([&](auto OB) { zero_o<decltype(OB)::value>(); });
+  static_for<C::kDBlocks * 16>([&](auto R) { zero_acc<kAccO + decltype(R)::value>(); });
 
-  float m_run[2] = {-INFINITY, -INFINITY};  // reference max of the raw scores <q,k>
-  float l_run[2] = {0.f, 0.f};              // this lane's share of the normaliser
+  float m_run = -INFINITY;  // reference max of the raw scores <q,k>
+  float l_run = 0.f;        // this lane's share of the normaliser
 
   // number of key tiles this workgroup walks, and the last one this wave needs
   const int n_keys = p.causal ? min(T, q0 + kBM) : T;
@@ -374,6 +366,7 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   int k_goff[C::kInstPerWave], v_goff[C::kInstPerWave];
 #pragma unroll
   for (int i = 0; i < C::kInstPerWave; ++i) {
+    const int lane = tid & 63;
     const int r = (wave * C::kInstPerWave + i) * C::kRowsPerInst + lane / C::kChunks;
     const int pc = lane % C::kChunks;  // chunk position this lane fills
     const int kc = pc ^ (r & (C::kChunks - 1));
@@ -384,7 +377,7 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   const i32x4 k_buf = make_raw_buffer(Kb, (unsigned)T * C::kRowBytes);
   const i32x4 v_buf = make_raw_buffer(Vb, (unsigned)T * C::kRowBytes);
-  // copy instruction i (of kInstPerWave) of this wave's share of tile kt
+  // copy instruction i (of kInstPerWave) of this wave's share of tile kt into ring byte offset stage_off
   auto issue_one = [&](const i32x4& buf, int kt, int stage_off, const int (&goff)[C::kInstPerWave], int i) {
     copy16_to_lds(buf, goff[i], kt * C::kTileBytes,
                   smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
@@ -393,120 +386,97 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
 #pragma unroll
     for (int i = 0; i < C::kInstPerWave; ++i) issue_one(buf, kt, stage_off, goff, i);
   };
-  auto k_stage_off = [&](int kt) { return (kt % kStagesK) * C::kTileBytes; };
-  auto v_stage_off = [&](int kt) { return C::kVBase + ((kt + kStagesV) % kStagesV) * C::kTileBytes; };
+  // tile kt of K sits in K stage kt % 4, tile kt of V in V stage kt % 4 (tile -1: stage 3)
+  auto k_stage_off = [&](int stage) { return stage * C::kTileBytes; };
+  auto v_stage_off = [&](int stage) { return C::kVBase + stage * C::kTileBytes; };
 
   auto mask_tile = [&](STile& s, int kt) {
     const int k0 = kt * kBN;
+    const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
+    const int qi = qw0 + l32;
+    const int lim = p.causal ? min(qi, T - 1) : T - 1;  // last visible key
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int qi = qw0 + nb * 32 + l32;
-      const int lim = p.causal ? min(qi, T - 1) : T - 1;  // last visible key
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = k0 + kb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
-          if (key > lim) s.a[kb][nb][i] = -INFINITY;
-        }
-    }
+      for (int i = 0; i < 16; ++i) {
+        const int key = k0 + kb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
+        if (key > lim) s.a[kb][i] = -INFINITY;
+      }
   };
   auto needs_mask = [&](int kt) { return (p.causal && kt * kBN + kBN - 1 > qw0) || (kt * kBN + kBN > T); };
 
   FragBase<D> fb;
-  fb.init(lane);
-  const float zero2[2] = {0.f, 0.f};
-  float mx[2] = {0.f, 0.f};
+  fb.init(tid & 63, (int)smem_addr);
+  float mx = 0.f;
 
   // ---- prologue: fill the rings, zero the V stage that stands in for "tile -1"
   // (its P is zero too, but 0 * garbage could be NaN), S(0) = K(0) Q^T.
-  for (int j = 0; j < kStagesK; ++j) issue_tile(k_buf, j, k_stage_off(j), k_goff);
-  for (int j = 0; j < kStagesV - 1; ++j) issue_tile(v_buf, j, v_stage_off(j), v_goff);
+  for (int j = 0; j < kStages; ++j) issue_tile(k_buf, j, k_stage_off(j), k_goff);
+  for (int j = 0; j < 2; ++j) issue_tile(v_buf, j, v_stage_off(j), v_goff);
   for (int i = tid * 16; i < C::kTileBytes; i += kThreads * 16)
-    *(i32x4*)(smem + v_stage_off(-1) + i) = (i32x4){0, 0, 0, 0};
+    *(i32x4*)(smem + v_stage_off(kStages - 1) + i) = (i32x4){0, 0, 0, 0};
   wait_copies_but<0>();
   __syncthreads();
 
   STile sA, sB;
   PTile pA, pB;
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) pA.a[kb][hf][nb] = pB.a[kb][hf][nb] = (i32x4){0, 0, 0, 0};
-  Pre3 kpre, vpre;
+  zero(pA);
+  clear(pB);
   {
-    const unsigned char* ks0 = smem + k_stage_off(0);
-    static_for<kAhead>([&](auto I) { kpre.f[decltype(I)::value] = read_kfrag<D, decltype(I)::value>(ks0, fb); });
-    qk_phase<D, false>(sA, ks0, kpre, qf, sA, pA, zero2, l_run, c2, fb);
+    static_for<kAhead>([&](auto I) { read_kfrag<D, 0, decltype(I)::value>(fb); });
+    qk_phase<D, 0, kStages - 1, false>(sA, sA, pA, 0.f, l_run, c2, fb);
     MODA_PIN();
     MODA_NOP(15);
     if (wave_last == 0 && needs_mask(0)) mask_tile(sA, 0);
-    const unsigned char* vs = smem + v_stage_off(-1);
-    static_for<kAhead>([&](auto I) { vpre.f[decltype(I)::value] = read_vfrag<D, decltype(I)::value>(vs, fb); });
   }
 
-  // ---- steady state.  Step kt (scores of tile kt are in `cur`, P of tile kt-1 in `pprev`):
+  // ---- steady state.  Step kt, kt % 4 == S (scores of tile kt are in `cur`, P of tile
+  // kt-1 in `pprev`):
   //   matrix pipe : O += P V (tile kt-1)            | S(next) = K Q^T (tile kt+1)
   //   vector ALUs : row max of tile kt, exp2 of its | exp2 of its second key block
   //                 first key block                 |
-  //   in between  : wait for the copies issued two steps ago, barrier, issue the copies
-  //                 of K tile kt+4 and V tile kt+2 into the stages just vacated.
+  //   in between  : wait for the copies issued two steps ago, barrier; the copies of
+  //                 K tile kt+4 and V tile kt+2 into the stages just vacated ride along
+  //                 with the second matrix phase.
   // The reference max is only raised when some row's tile max exceeds it by more than
   // 2^8 in the exp2 domain; P may then exceed 1 (bounded by 256), which fp32 sums and
   // bf16 P hold without loss, and the final division is unchanged.  Raising it is the
   // rare path: the pending P V is finished first, then the accumulators are rescaled.
-  auto step = [&](int kt, STile& cur, STile& nxt, const PTile& pprev, PTile& pcur) {
-    constexpr int NFV = 4 * C::kDBlocks;
+  auto step = [&](auto SI, int kt, STile& cur, STile& nxt, const PTile& pprev, PTile& pcur) {
+    constexpr int S = decltype(SI)::value;
+    constexpr int VS_PREV = (S + 3) % kStages;  // V tile kt-1
+    constexpr int KS_NEXT = (S + 1) % kStages;  // K tile kt+1
+    constexpr int VS_CUR = S;                   // V tile kt
+    constexpr int NFV = C::kNFV;
     constexpr int HEAD = C::kDBlocks;  // V fragments of the first 16 keys
     if (kt <= wave_last) {
-      const unsigned char* vs = smem + v_stage_off(kt - 1);
-      i32x4 vf[NFV];
-      #pragma unroll
-      for (int i = 0; i < kAhead; ++i) vf[i] = vpre.f[i];
-      pv_phase<D, 0, HEAD, 1>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
-      const bool raise = (mx[0] - m_run[0]) * c2 > 8.f || (mx[1] - m_run[1]) * c2 > 8.f;
+      pv_phase<D, VS_PREV, KS_NEXT, 0, HEAD, 1>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
+      const bool raise = (mx - m_run) * c2 > 8.f;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) {
         // Rare path (always taken for the first tile, where m_run = -inf).
-        pv_phase<D, HEAD, NFV, 0>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
+        pv_phase<D, VS_PREV, KS_NEXT, HEAD, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
         MODA_PIN();
         MODA_NOP(15);  // every MFMA above has retired
-        float alpha[2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          const float m_new = fmaxf(m_run[nb], mx[nb]);
-          alpha[nb] = fast_exp2((m_run[nb] - m_new) * c2);  // 0 when m_run = -inf
-          m_run[nb] = m_new;
-          l_run[nb] *= alpha[nb];
-        }
-        static_for<C::kDBlocks * 2>([&](auto OB) {
-          constexpr int ob = decltype(OB)::value;
-          scale_o<ob>(alpha[ob & 1]);
-        });
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * c2);  // 0 when m_run = -inf
+        m_run = m_new;
+        l_run *= alpha;
+        static_for<C::kDBlocks * 16>([&](auto R) { scale_acc<kAccO + decltype(R)::value>(alpha); });
         MODA_PIN();
         MODA_NOP(7);  // register writes settle before the next MFMA
-        const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
-        static_for<16>([&](auto Q) { exp_pair<decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
+        const float mc = m_run * c2;
+        static_for<8>([&](auto Q) { exp_pair<decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
       } else {
-        const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
-        pv_phase<D, HEAD, NFV, 2>(vs, vf, pprev, cur, pcur, mc, l_run, mx, c2, fb);
+        const float mc = m_run * c2;
+        pv_phase<D, VS_PREV, KS_NEXT, HEAD, NFV, 2>(pprev, cur, pcur, mc, l_run, mx, c2, fb);
       }
       // (for this wave's last tile the next K tile is not needed; it is read and
       //  multiplied all the same, which keeps the loop body free of branches)
-      const unsigned char* ksn = smem + k_stage_off(kt + 1);
-      static_for<kAhead>([&](auto I) { kpre.f[decltype(I)::value] = read_kfrag<D, decltype(I)::value>(ksn, fb); });
     } else if (kt == wave_last + 1) {
-      // this wave's last tile: only its P V is left
-      const unsigned char* vs = smem + v_stage_off(kt - 1);
-      i32x4 vf[NFV];
-      #pragma unroll
-      for (int i = 0; i < kAhead; ++i) vf[i] = vpre.f[i];
-      pv_phase<D, 0, NFV, 0>(vs, vf, pprev, cur, pcur, zero2, l_run, mx, c2, fb);
-      clear(kpre);
+      // this wave's last tile: only its P V is left (the K fragments it requests are never used)
+      pv_phase<D, VS_PREV, KS_NEXT, 0, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
       clear(pcur);
     } else {
-      clear(kpre);
       clear(pcur);
     }
 
@@ -514,12 +484,12 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     // out of range of the raw buffer: nothing is fetched), so "all but the newest
     // 2*kInstPerWave copies have landed" always means: K tile kt+2 and V tile kt, which
     // are read next, are complete.
-    const int kt_k = kt + kStagesK, kt_v = kt + kStagesV - 1;
-    const int so_k = k_stage_off(kt_k), so_v = v_stage_off(kt_v);
+    const int kt_k = kt + kStages, kt_v = kt + 2;
+    const int so_k = k_stage_off(S), so_v = v_stage_off((S + 2) % kStages);
     if (kt < nt) {
       wait_copies_but<2 * C::kInstPerWave>();
       __syncthreads();
-      // every wave is past the first half of step kt: K tile kt and V tile kt-1 are dead
+      // every wave is past the first half of step kt: K tile kt and V tile kt-2 are dead
       if (kt > wave_last) {
         issue_tile(k_buf, kt_k, so_k, k_goff);
         issue_tile(v_buf, kt_v, so_v, v_goff);
@@ -527,7 +497,7 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
     }
 
     if (kt <= wave_last) {
-      const float mc[2] = {m_run[0] * c2, m_run[1] * c2};
+      const float mc = m_run * c2;
       // this step's copies ride along, one after every fourth MFMA
       auto hook = [&](auto M) {
         constexpr int m = decltype(M)::value;
@@ -537,29 +507,30 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
           else issue_one(v_buf, kt_v, so_v, v_goff, i - C::kInstPerWave);
         }
       };
-      qk_phase<D, true>(nxt, smem + k_stage_off(kt + 1), kpre, qf, cur, pcur, mc, l_run, c2, fb, hook);
+      qk_phase<D, KS_NEXT, VS_CUR, true>(nxt, cur, pcur, mc, l_run, c2, fb, hook);
       if (kt + 1 == wave_last && needs_mask(kt + 1)) {
         MODA_PIN();
         MODA_NOP(15);
         mask_tile(nxt, kt + 1);
       }
-      const unsigned char* vs = smem + v_stage_off(kt);
-      static_for<kAhead>([&](auto I) { vpre.f[decltype(I)::value] = read_vfrag<D, decltype(I)::value>(vs, fb); });
     } else {
       clear(nxt);
-      clear(vpre);
     }
   };
-  for (int kt = 0; kt <= nt; kt += 2) {
-    step(kt, sA, sB, pA, pB);
-    if (kt + 1 <= nt) step(kt + 1, sB, sA, pB, pA);
+  for (int kt = 0; kt <= nt; kt += 4) {
+    step(std::integral_constant<int, 0>{}, kt, sA, sB, pA, pB);
+    if (kt + 1 <= nt) step(std::integral_constant<int, 1>{}, kt + 1, sB, sA, pB, pA);
+    if (kt + 2 <= nt) step(std::integral_constant<int, 2>{}, kt + 2, sA, sB, pA, pB);
+    if (kt + 3 <= nt) step(std::integral_constant<int, 3>{}, kt + 3, sB, sA, pB, pA);
   }
   MODA_PIN();
   MODA_NOP(15);          // accumulators final before they are read out
+  lds_wait<0>();         // fragment reads requested but never used have landed
   wait_copies_but<0>();  // the ring is reused below: no copy may still be landing in it
   __syncthreads();
 
   // ================= epilogue: accumulator layout -> row-major, depth slots, store
+  const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
   unsigned char* xw = smem + wave * C::kXWave;
   float* ml = (float*)(xw + 32 * C::kXRow);
   constexpr int LPR = C::kChunks;   // lanes per query row: each owns 8 channels (16 B)
@@ -573,22 +544,20 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   char* Ob = (char*)p.O + (size_t)bh * T * C::kRowBytes;
   float* LSEb = p.LSE + (size_t)bh * T;
 
-  // accumulators of query block NB -> this wave's exchange buffer, (m, l) per row
-  auto exchange = [&](auto NB) {
-    constexpr int nb = decltype(NB)::value;
-    const float l_tot = pair_sum(l_run[nb]);
+  // accumulators -> this wave's exchange buffer, (m, l) per row
+  auto exchange = [&]() {
+    const float l_tot = pair_sum(l_run);
     static_for<C::kDBlocks>([&](auto DBI) {
       constexpr int db = decltype(DBI)::value;
-      float x[16];
-      read_o<db * 2 + nb>(x);
-#pragma unroll
-      for (int bq = 0; bq < 4; ++bq) {
-        f32x4 v = {x[4 * bq], x[4 * bq + 1], x[4 * bq + 2], x[4 * bq + 3]};
+      static_for<4>([&](auto BQ) {
+        constexpr int bq = decltype(BQ)::value;
+        constexpr int r0 = kAccO + db * 16 + bq * 4;
+        f32x4 v = {read_acc<r0>(), read_acc<r0 + 1>(), read_acc<r0 + 2>(), read_acc<r0 + 3>()};
         *(f32x4*)(xw + l32 * C::kXRow + (db * 32 + bq * 8 + hi * 4) * 4) = v;
-      }
+      });
     });
     if (hi == 0) {
-      ml[2 * l32] = m_run[nb];
+      ml[2 * l32] = m_run;
       ml[2 * l32 + 1] = l_tot;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -614,28 +583,21 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
     }
   };
-  constexpr int NIT = 32 / RPS;  // row steps per query block
+  constexpr int NIT = 32 / RPS;  // row steps of the wave's 32 queries
 
+  exchange();
   if (L == 0) {
-    static_for<2>([&](auto NB) {
-      constexpr int nb = decltype(NB)::value;
-      exchange(NB);
-      for (int it = 0; it < NIT; ++it) {
-        const int row = it * RPS + rg;
-        load_row(row);
-        store_row(qw0 + nb * 32 + row);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    });
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPS + rg;
+      load_row(row);
+      store_row(qw0 + row);
+    }
     return;
   }
 
-  // ---- depth slots.  Work items (query block, row step, chunk of kDepthChunk slots) are
-  // walked in order with the NEXT item's loads already in flight while the current
-  // item is folded into the row's (m, l, o): the phase is bound by memory latency, so
-  // the loads of one item must never wait for the arithmetic of another.
+  // ---- depth slots.  Work items (row step, chunk of kDepthChunk slots) are walked in
+  // order with the NEXT item's loads already in flight while the current item is folded
+  // into the row's (m, l, o); the other wave of the SIMD covers what latency is left.
   struct DepthBuf {
     u32x4 q;
     u32x4 k[kDepthChunk], v[kDepthChunk];
@@ -649,8 +611,8 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
       (void*)Vdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
-  auto issue = [&](int nb, int it, int c, DepthBuf& buf) {
-    const int tc = min(qw0 + nb * 32 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
+  auto issue = [&](int it, int c, DepthBuf& buf) {
+    const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
     buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
     const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
     const int soff = c * kDepthChunk * C::kRowBytes;
@@ -663,7 +625,7 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   };
   auto fold = [&](int c, const DepthBuf& buf) {
     float sc[kDepthChunk];
-    float mx = m;
+    float mx2 = m;
 #pragma unroll
     for (int i = 0; i < kDepthChunk; ++i) {
       float a = dot2_bf16(buf.q[0], buf.k[i][0], 0.f);
@@ -672,11 +634,11 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       a = dot2_bf16(buf.q[3], buf.k[i][3], a);
       a = group_sum<LPR>(a);
       sc[i] = (c * kDepthChunk + i < L) ? a : -INFINITY;
-      mx = fmaxf(mx, sc[i]);
+      mx2 = fmaxf(mx2, sc[i]);
     }
-    const float al = fast_exp2((m - mx) * c2);
-    const float mc = mx * c2;
-    m = mx;
+    const float al = fast_exp2((m - mx2) * c2);
+    const float mc = mx2 * c2;
+    m = mx2;
     l *= al;
 #pragma unroll
     for (int k = 0; k < 8; ++k) o[k] *= al;
@@ -695,27 +657,23 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
       }
     }
   };
-  // Item cursors: (nb, it, c) is the item being folded, (nbi, iti, ci) the next one
-  // whose loads are to be issued (two items ahead).  Past the end the issue cursor
-  // stays on the last item (its loads are repeated and ignored): a conditional issue
-  // would make the compiler wait for the older loads as if the newer ones were not there.
-  int nb = 0, it = 0, c = 0;
-  int nbi = 0, iti = 0, ci = 0;
-  auto advance = [&](int& b_, int& i_, int& c_) {
+  // Item cursors: (it, c) is the item being folded, (iti, ci) the next one whose loads
+  // are to be issued (one item ahead).  Past the end the issue cursor stays on the last
+  // item (its loads are repeated and ignored): a conditional issue would make the
+  // compiler wait for the older loads as if the newer ones were not there.
+  int it = 0, c = 0;
+  int iti = 0, ci = 0;
+  auto advance = [&](int& i_, int& c_) {
     if (++c_ == nch) {
       c_ = 0;
-      if (++i_ == NIT) {
-        i_ = 0;
-        ++b_;
-      }
+      ++i_;
     }
   };
   auto issue_next = [&](DepthBuf& buf) {
-    issue(nbi, iti, ci, buf);
-    int b2 = nbi, i2 = iti, c2n = ci;
-    advance(b2, i2, c2n);
-    if (b2 < 2) {
-      nbi = b2;
+    issue(iti, ci, buf);
+    int i2 = iti, c2n = ci;
+    advance(i2, c2n);
+    if (i2 < NIT) {
       iti = i2;
       ci = c2n;
     }
@@ -724,30 +682,18 @@ __global__ __launch_bounds__(kThreads, 1) void moda_fwd_bf16_kernel(FwdParams p)
   // fold the current item from `cur`; false when it was the last one
   auto one = [&](const DepthBuf& cur, DepthBuf& refill) -> bool {
     issue_next(refill);
-    if (it == 0 && c == 0) {
-      if (nb == 0) {
-        exchange(std::integral_constant<int, 0>{});
-      } else {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        exchange(std::integral_constant<int, 1>{});
-      }
-    }
     const int row = it * RPS + rg;
     if (c == 0) load_row(row);
     fold(c, cur);
-    if (c == nch - 1) store_row(qw0 + nb * 32 + row);
-    advance(nb, it, c);
-    return nb < 2;
+    if (c == nch - 1) store_row(qw0 + row);
+    advance(it, c);
+    return it < NIT;
   };
-  DepthBuf bufA, bufB, bufC;
+  DepthBuf bufA, bufB;
   issue_next(bufA);
-  issue_next(bufB);
   while (true) {
-    if (!one(bufA, bufC)) break;
+    if (!one(bufA, bufB)) break;
     if (!one(bufB, bufA)) break;
-    if (!one(bufC, bufB)) break;
   }
 }
 
