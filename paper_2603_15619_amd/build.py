@@ -29,38 +29,117 @@ def _compile(src):
 
 
 # Sources whose inline assembly owns ALL accumulation registers by name (see
-# csrc/moda_fwd_regs.h).  The compiler is not told that they hold live values, so the
-# build verifies on the generated assembly that it never touches one itself, and that
-# nothing was spilled to scratch memory.
+# csrc/moda_fwd_regs.h) up to the point where the kernel emits the marker comment
+# ACC_RELEASE_MARKER.  The compiler is not told that they hold live values, so the build
+# verifies on the generated assembly, per kernel and on its control-flow graph, that
+#   - no instruction that can execute before the marker touches an accumulation
+#     register unless it sits inside one of the hand-written assembly statements,
+#   - no hand-written statement that names an accumulation register can execute after
+#     the marker (from there on the registers are the compiler's),
+#   - nothing was spilled to scratch memory.
 NAMED_ACC_SOURCES = ("moda_fwd_bf16.hip",)
-FIRST_NAMED_ACC = 0
+ACC_RELEASE_MARKER = "MODA_ACC_REGISTERS_RELEASED"
 
 
-def check_named_acc_registers(src) -> None:
+def _kernel_bodies(asm_path):
+    """Yields (name, [(line_no, text)]) for every function of the assembly file."""
     import re
 
-    asm = os.path.join(OBJ, os.path.basename(src)[:-4] + ".s")
-    subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", asm], check=True,
-                   stderr=subprocess.DEVNULL)
-    in_asm = False
-    pat = re.compile(r"\ba(?:\[(\d+):(\d+)\]|(\d+))\b")
-    for n, line in enumerate(open(asm), 1):
+    name, body = None, []
+    for n, line in enumerate(open(asm_path), 1):
+        if name is None:
+            m = re.match(r"^(_Z\w+):", line)
+            if m:
+                name, body = m.group(1), []
+        elif line.startswith(".Lfunc_end"):
+            yield name, body
+            name = None
+        else:
+            body.append((n, line.rstrip("\n")))
+
+
+def _check_kernel(asm_path, name, body) -> None:
+    import re
+
+    acc = re.compile(r"\ba(?:\[\d+:\d+\]|\d+)\b")
+    # instruction stream: (line_no, text, hand_written)
+    ins, labels, in_asm = [], {}, False
+    for n, line in body:
         if "#ASMSTART" in line:
             in_asm = True
             continue
         if "#ASMEND" in line:
             in_asm = False
             continue
-        code = line.split(";")[0]
-        if in_asm or not code.strip() or code.lstrip().startswith("."):
+        if in_asm and ACC_RELEASE_MARKER in line:
+            ins.append((n, ACC_RELEASE_MARKER, True))
             continue
-        for m in pat.finditer(code):
-            hi = int(m.group(2) or m.group(3))
-            if hi >= FIRST_NAMED_ACC:
-                raise RuntimeError("%s:%d: compiler-allocated use of a%d collides with the named "
-                                   "accumulation registers: %s" % (asm, n, hi, line.strip()))
-        if code.strip().startswith(("scratch_", "buffer_store", "buffer_load")) and "off" in code and "s[0:3]" in code:
-            raise RuntimeError("%s:%d: register spill to scratch memory: %s" % (asm, n, line.strip()))
+        code = line.split(";")[0].strip()
+        if not code:
+            continue
+        m = re.match(r"^(\.LBB\d+_\d+):", code)
+        if m:
+            labels[m.group(1)] = len(ins)
+            continue
+        if code.startswith("."):
+            continue
+        ins.append((n, code, in_asm))
+    markers = [i for i, x in enumerate(ins) if x[1] == ACC_RELEASE_MARKER]
+    if len(markers) != 1:
+        raise RuntimeError("%s: %s: expected exactly one %s, found %d"
+                           % (asm_path, name, ACC_RELEASE_MARKER, len(markers)))
+    marker = markers[0]
+
+    def successors(i):
+        op = ins[i][1].split()[0]
+        if op in ("s_setpc_b64", "s_swappc_b64", "s_call_b64") or op.startswith("s_cbranch_i_fork"):
+            raise RuntimeError("%s:%d: indirect control flow: %s" % (asm_path, ins[i][0], ins[i][1]))
+        if op == "s_endpgm":
+            return []
+        if op == "s_branch":
+            return [labels[ins[i][1].split()[1]]]
+        out = [i + 1] if i + 1 < len(ins) else []
+        if op.startswith("s_cbranch"):
+            out.append(labels[ins[i][1].split()[1]])
+        return out
+
+    def reach(start, stop=None):
+        seen, todo = set(), [start]
+        while todo:
+            i = todo.pop()
+            if i in seen or i == stop:
+                continue
+            seen.add(i)
+            todo.extend(successors(i))
+        return seen
+
+    before = reach(0, stop=marker)          # can execute before the marker
+    after = reach(marker)                   # can execute after it
+    for i in sorted(before):
+        n, code, hand = ins[i]
+        if not hand and acc.search(code):
+            raise RuntimeError("%s:%d: %s: compiler-allocated accumulation register while the named "
+                               "ones are live: %s" % (asm_path, n, name, code))
+    for i in sorted(after):
+        n, code, hand = ins[i]
+        if hand and acc.search(code):
+            raise RuntimeError("%s:%d: %s: named accumulation register used after they were released: %s"
+                               % (asm_path, n, name, code))
+
+
+def check_named_acc_registers(src) -> None:
+    asm = os.path.join(OBJ, os.path.basename(src)[:-4] + ".s")
+    subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", asm], check=True,
+                   stderr=subprocess.DEVNULL)
+    n_kernels = 0
+    for name, body in _kernel_bodies(asm):
+        _check_kernel(asm, name, body)
+        n_kernels += 1
+    if n_kernels == 0:
+        raise RuntimeError("%s: no kernel found" % asm)
+    for line in open(asm):
+        if line.startswith("; ScratchSize:") and int(line.split(":")[1]) != 0:
+            raise RuntimeError("%s: register spill to scratch memory (%s)" % (asm, line.strip()))
 
 
 def build_libmoda() -> str:

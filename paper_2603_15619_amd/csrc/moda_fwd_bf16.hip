@@ -586,6 +586,9 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   constexpr int NIT = 32 / RPS;  // row steps of the wave's 32 queries
 
   exchange();
+  // From here on the accumulation registers are the compiler's (it parks depth K/V
+  // loads in them); the build step checks that on the generated code.
+  asm volatile("; MODA_ACC_REGISTERS_RELEASED" ::: "memory");
   if (L == 0) {
     for (int it = 0; it < NIT; ++it) {
       const int row = it * RPS + rg;
@@ -596,8 +599,10 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   }
 
   // ---- depth slots.  Work items (row step, chunk of kDepthChunk slots) are walked in
-  // order with the NEXT item's loads already in flight while the current item is folded
-  // into the row's (m, l, o); the other wave of the SIMD covers what latency is left.
+  // order with the loads of the next TWO items in flight while the current item is
+  // folded into the row's (m, l, o): the phase is bound by memory latency, i.e. by the
+  // bytes a compute unit keeps in flight, and the 128 accumulation registers that the
+  // key loop no longer needs hold most of them.
   struct DepthBuf {
     u32x4 q;
     u32x4 k[kDepthChunk], v[kDepthChunk];
@@ -658,7 +663,7 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
     }
   };
   // Item cursors: (it, c) is the item being folded, (iti, ci) the next one whose loads
-  // are to be issued (one item ahead).  Past the end the issue cursor stays on the last
+  // are to be issued (two items ahead).  Past the end the issue cursor stays on the last
   // item (its loads are repeated and ignored): a conditional issue would make the
   // compiler wait for the older loads as if the newer ones were not there.
   int it = 0, c = 0;
@@ -689,11 +694,13 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
     advance(it, c);
     return it < NIT;
   };
-  DepthBuf bufA, bufB;
+  DepthBuf bufA, bufB, bufC;
   issue_next(bufA);
+  issue_next(bufB);
   while (true) {
-    if (!one(bufA, bufB)) break;
+    if (!one(bufA, bufC)) break;
     if (!one(bufB, bufA)) break;
+    if (!one(bufC, bufB)) break;
   }
 }
 
