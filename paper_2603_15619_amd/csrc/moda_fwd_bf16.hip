@@ -68,6 +68,10 @@ struct FwdCfg {
   static constexpr int kLds = kRingBytes > kXBytes ? kRingBytes : kXBytes;
   static constexpr int kRowsPerInst = 64 / kChunks;                 // tile rows per wave copy instruction
   static constexpr int kInstPerWave = kBN / kRowsPerInst / kWaves;  // copy instructions per wave per tile
+  // V tile: segment permutation of row r (see the layout comment below)
+  static constexpr int kSegs = kRowBytes / 64;        // 64-byte segments per row (4 or 2)
+  static constexpr int kRowsPer256 = 256 / kRowBytes; // rows per sweep over all banks (1 or 2)
+  __device__ static __forceinline__ int vswz(int r) { return (r / kRowsPer256) & (kSegs - 1); }
   static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
 };
 
@@ -135,8 +139,11 @@ __device__ __forceinline__ void wait_copies_but() {  // all but the N most recen
 //   K tile: chunk c of row r sits at chunk position c ^ (r & (chunks-1)); the MFMA
 //           A-operand read (consecutive lanes = consecutive rows, same c) is then
 //           conflict free.
-//   V tile: the 32-byte pair (c >> 1) sits at pair position (c >> 1) ^ (r & (chunks/2-1));
-//           the transposing read (16 lanes read 4 rows x 32 B) is then conflict free.
+//   V tile: the 64-byte segment (c >> 2) sits at segment position (c >> 2) ^ vswz(r).  The
+//           transposing read takes 2 cycles of 32 lanes; in one cycle the lanes read 4
+//           consecutive rows x one 64-byte segment, and vswz spreads those 4 rows over the
+//           4 groups of 16 banks (measured: the 32-byte-pair permutation used before cost a
+//           2-way conflict on every transposing read).
 // Every fragment address is (per-lane base ^ constant), kept in a register, plus
 // stage offset + constant in the instruction's immediate.
 template <int D>
@@ -153,8 +160,7 @@ struct FragBase {
     // V fragment (ks, db): transposing read, see read_vfrag
     const int r8 = hi * 4 + ((lane & 15) >> 2);  // row inside the 16-key group (first read)
     const int grp = (lane >> 4) & 1;             // which 16 channels of the 32-channel block
-    const int x = r8 & (C::kChunks / 2 - 1);
-    const int vbase = r8 * C::kRowBytes + ((grp ^ x) << 5) + (lane & 3) * 8;
+    const int vbase = r8 * C::kRowBytes + (C::vswz(r8) << 6) + grp * 32 + (lane & 3) * 8;
 #pragma unroll
     for (int db = 0; db < C::kDBlocks; ++db) v[db] = smem_addr + C::kVBase + (vbase ^ (db << 6));
   }
@@ -370,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
     const int r = (wave * C::kInstPerWave + i) * C::kRowsPerInst + lane / C::kChunks;
     const int pc = lane % C::kChunks;  // chunk position this lane fills
     const int kc = pc ^ (r & (C::kChunks - 1));
-    const int vc = (((pc >> 1) ^ (r & (C::kChunks / 2 - 1))) << 1) | (pc & 1);
+    const int vc = (((pc >> 2) ^ C::vswz(r)) << 2) | (pc & 3);
     k_goff[i] = r * C::kRowBytes + kc * 16;
     v_goff[i] = r * C::kRowBytes + vc * 16;
   }
