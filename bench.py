@@ -195,10 +195,10 @@ def main():
     if args.workload == "sweep":
         return run_sweep(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
-    if args.workload.startswith("bwd_"):
-        return run_backward(args, B, Hq, Hk, T, d, L, dtype)
     if args.depth_count is not None:
         L = args.depth_count
+    if args.workload.startswith("bwd_"):
+        return run_backward(args, B, Hq, Hk, T, d, L, dtype)
     inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=2, device="cuda")
     O = torch.empty_like(inp["Q"])
     LSE = torch.empty((B, Hq, T), dtype=torch.float32, device="cuda")

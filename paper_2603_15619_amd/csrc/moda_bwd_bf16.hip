@@ -62,7 +62,7 @@ __device__ __forceinline__ bf16x8 pack8(const float (&x)[8]) {
 // Workgroup = 128 keys (4 waves x 32 keys).  Accumulators hold dK^T, dV^T
 // ([channel][key]: a lane owns one key and 64 of its channels).
 template <int D>
-__global__ __launch_bounds__(256, 1) void moda_bwd_dkdv_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   using Tl = Tile<D>;
   using C = BwdCfg<D>;
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
@@ -132,22 +132,20 @@ __global__ __launch_bounds__(256, 1) void moda_bwd_dkdv_kernel(BwdParams p) {
     const float* lse_s = aux + stage * 128;
     const float* del_s = lse_s + 64;
 
-    f32x16 s[2], dp[2];
+    const int key = kw0 + l32;
+    // one 32-query block at a time: S, dP (recomputed), P and dS for this lane's key and
+    // 16 queries, then dV^T += dO^T P and dK^T += Q^T dS over those 32 queries
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+      f32x16 s, dp;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[qb][i] = dp[qb][i] = 0.f;
+      for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
 #pragma unroll
       for (int st = 0; st < Tl::kDSteps; ++st) {
-        s[qb] = mfma_bf16(Tl::row_frag(qtile, qb, st, lane), kf[st], s[qb]);
-        dp[qb] = mfma_bf16(Tl::row_frag(dotile, qb, st, lane), vf[st], dp[qb]);
+        s = mfma_bf16(Tl::row_frag(qtile, qb, st, lane), kf[st], s);
+        dp = mfma_bf16(Tl::row_frag(dotile, qb, st, lane), vf[st], dp);
       }
-    }
-    // P and dS for this lane's key and 2 x 16 queries
-    bf16x8 pb[2][2], dsb[2][2];  // [query block][16-query half]
-    const int key = kw0 + l32;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+      bf16x8 pb[2], dsb[2];  // [16-query half]
       float pv[16], dsv[16];
 #pragma unroll
       for (int b4 = 0; b4 < 4; ++b4) {
@@ -158,9 +156,9 @@ __global__ __launch_bounds__(256, 1) void moda_bwd_dkdv_kernel(BwdParams p) {
           const int i = b4 * 4 + r;
           const int q = q0 + qb * 32 + b4 * 8 + hi * 4 + r;
           const bool vis = q < T && (!p.causal || key <= q);
-          const float pe = vis ? fast_exp2(s[qb][i] * c2 - l4[r]) : 0.f;
+          const float pe = vis ? fast_exp2(s[i] * c2 - l4[r]) : 0.f;
           pv[i] = pe;
-          dsv[i] = pe * (dp[qb][i] - d4[r]);
+          dsv[i] = pe * (dp[i] - d4[r]);
         }
       }
 #pragma unroll
@@ -171,18 +169,17 @@ __global__ __launch_bounds__(256, 1) void moda_bwd_dkdv_kernel(BwdParams p) {
           a[k] = pv[hf * 8 + k];
           b[k] = dsv[hf * 8 + k];
         }
-        pb[qb][hf] = pack8(a);
-        dsb[qb][hf] = pack8(b);
+        pb[hf] = pack8(a);
+        dsb[hf] = pack8(b);
       }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int db = 0; db < Tl::kDBlocks; ++db) {
+          dv[db] = mfma_bf16(Tl::tr_frag(dotile, qb * 2 + hf, db, lane), pb[hf], dv[db]);
+          dk[db] = mfma_bf16(Tl::tr_frag(qtile, qb * 2 + hf, db, lane), dsb[hf], dk[db]);
+        }
     }
-    // dV^T += dO^T P,  dK^T += Q^T dS   (contraction over the tile's 64 queries)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int db = 0; db < Tl::kDBlocks; ++db) {
-        dv[db] = mfma_bf16(Tl::tr_frag(dotile, ks, db, lane), pb[ks >> 1][ks & 1], dv[db]);
-        dk[db] = mfma_bf16(Tl::tr_frag(qtile, ks, db, lane), dsb[ks >> 1][ks & 1], dk[db]);
-      }
   }
   __syncthreads();
 
@@ -226,7 +223,7 @@ __global__ __launch_bounds__(256, 1) void moda_bwd_dkdv_kernel(BwdParams p) {
 // Workgroup = 128 queries (4 waves x 32 queries).  Accumulators hold dQ^T
 // ([channel][query]: a lane owns one query).
 template <int D>
-__global__ __launch_bounds__(256, 1) void moda_bwd_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   using Tl = Tile<D>;
   using C = BwdCfg<D>;
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
