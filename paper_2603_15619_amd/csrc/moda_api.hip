@@ -1,5 +1,6 @@
 // libmoda C ABI: argument validation and kernel dispatch (host code only).
 #include <math.h>
+#include <stdlib.h>
 
 #include "../../include/moda.h"
 #include "moda_launch.h"
@@ -24,6 +25,17 @@ moda_status check_shape(const moda_shape* s) {
   const unsigned long long slots = s->depth_alloc > 0 ? (unsigned long long)s->depth_alloc : 1ull;
   if ((unsigned long long)s->T * slots * (unsigned long long)s->d * esz >= (1ull << 32)) return MODA_ERR_UNSUPPORTED;
   return MODA_OK;
+}
+
+// Geometry of the bf16 forward kernel (see moda_fwd_bf16.hip).  MODA_FWD_WAVES = 4 or 8
+// overrides the choice (for experiments).
+int fwd_waves_per_workgroup(const moda_shape* s) {
+  if (const char* e = getenv("MODA_FWD_WAVES")) {
+    const int w = atoi(e);
+    if (w == 4 || w == 8) return w;
+  }
+  (void)s;
+  return 8;
 }
 
 float resolve_scale(const moda_shape* s) {
@@ -75,11 +87,12 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
   p.causal = s->causal;
   p.scale = resolve_scale(s);
   p.scale_log2 = p.scale * 1.4426950408889634f;
-  const int rows = moda::fwd_bf16_tile_rows();
+  const int waves = fwd_waves_per_workgroup(s);
+  const int rows = moda::fwd_bf16_tile_rows(waves);
   p.n_qtiles = (s->T + rows - 1) / rows;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipError_t e = (s->dtype == MODA_BF16) ? moda::launch_fwd_bf16(p, s->d, stream)
+  hipError_t e = (s->dtype == MODA_BF16) ? moda::launch_fwd_bf16(p, s->d, waves, stream)
                                          : moda::launch_fwd_f32(p, s->d, stream);
   return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
 }

@@ -36,12 +36,9 @@
 
 namespace moda {
 
-constexpr int kWaves = 8;
-constexpr int kThreads = kWaves * 64;
 constexpr int kQPerWave = 32;            // one 32-query MFMA block per wave
-constexpr int kBM = kWaves * kQPerWave;  // 256 queries per workgroup
 constexpr int kBN = 64;                  // keys per LDS tile
-constexpr int kStages = 4;               // LDS ring depth, K and V each; the key loop is unrolled by it
+constexpr int kUnroll = 4;               // the key loop is unrolled over 4 steps (a multiple of every ring depth)
 // cache policy of loads whose data is used exactly once (depth K/V): non-temporal, so
 // that the stream does not push the re-used sequence K/V tiles out of the L2
 constexpr int kStreamOnce = 2;
@@ -49,11 +46,34 @@ constexpr int kDepthChunk = 5;           // depth slots per work item of the dep
 constexpr int kAhead = 4;                // fragments read from LDS ahead of the MFMA that consumes them
 static_assert(kAhead < kSlots - 1, "a slot is refilled only after the MFMA that read it was issued");
 
-template <int D>
+// Two geometries:
+//   W = 8: one workgroup of 8 waves (256 queries) per compute unit, K and V rings of 4 stages
+//          (128 KB at d = 128); copies run two steps ahead of their use.
+//   W = 4: workgroups of 4 waves (128 queries), rings of 2 stages (64 KB), so that TWO
+//          workgroups share a compute unit (still two waves per SIMD): while one of them is in
+//          its depth phase, which is bound by memory latency, the other keeps the matrix pipe
+//          busy.  Copies run one step ahead; every K/V tile is fetched from L2 twice as often.
+template <int D, int W>
 struct FwdCfg {
+  static constexpr int kD = D;
+  static constexpr int kWaves = W;
+  static constexpr int kThreads = W * 64;
+  static constexpr int kBM = W * kQPerWave;        // queries per workgroup
+  static constexpr int kStages = W == 8 ? 4 : 2;   // LDS ring depth, K and V each
+  static constexpr int kVAhead = W == 8 ? 2 : 1;   // V tile kt + kVAhead is requested in step kt
+  static_assert(kUnroll % kStages == 0, "ring stage of a step is a compile-time constant");
   static constexpr int kChunks = D / 8;          // 16-byte chunks per K/V row
   static constexpr int kRowBytes = D * 2;
-  static constexpr int kTileBytes = kBN * kRowBytes;
+  static constexpr int kGTileBytes = kBN * kRowBytes;  // a tile in global memory
+  // A tile in LDS is made of 1 KB pieces (what one wave copy instruction moves: 4 rows at
+  // d = 128, 8 at d = 64); the pieces of a K tile at d = 128 are 64 bytes apart (see the
+  // layout comment), all others adjacent.
+  static constexpr int kPieceRows = 1024 / kRowBytes;
+  static constexpr int kKPieceStride = 1024 + (D == 128 ? 64 : 0);
+  static constexpr int kVPieceStride = 1024;
+  static constexpr int kKTileBytes = kBN / kPieceRows * kKPieceStride;  // a K tile (ring stage) in LDS
+  static constexpr int kVTileBytes = kBN / kPieceRows * kVPieceStride;  // a V tile (ring stage) in LDS
+  static constexpr int kKRegs = D == 128 ? 2 : D / 16;  // per-lane K fragment base addresses
   static constexpr int kDSteps = D / 16;         // MFMA k-steps over the head dim
   static constexpr int kDBlocks = D / 32;        // 32-wide output blocks over the head dim
   static constexpr int kNFK = kDSteps * 2;       // K fragments (= MFMAs of S^T = K Q^T) per tile
@@ -63,15 +83,18 @@ struct FwdCfg {
   static constexpr int kXRow = D * 4 + 16;
   static constexpr int kXWave = 32 * kXRow + 32 * 8;  // + (m, l) per row
   static constexpr int kXBytes = kWaves * kXWave;
-  static constexpr int kVBase = kStages * kTileBytes;  // V ring follows the K ring
-  static constexpr int kRingBytes = 2 * kStages * kTileBytes;
+  static constexpr int kVBase = kStages * kKTileBytes;  // V ring follows the K ring
+  static constexpr int kRingBytes = kStages * (kKTileBytes + kVTileBytes);
   static constexpr int kLds = kRingBytes > kXBytes ? kRingBytes : kXBytes;
-  static constexpr int kRowsPerInst = 64 / kChunks;                 // tile rows per wave copy instruction
-  static constexpr int kInstPerWave = kBN / kRowsPerInst / kWaves;  // copy instructions per wave per tile
+  static_assert((W == 8 ? 1 : 2) * kLds <= 160 * 1024, "workgroups per compute unit x LDS");
+  static constexpr int kInstPerWave = kBN / kPieceRows / kWaves;  // copy instructions (pieces) per wave per tile
+  // copy instructions of a wave that may still be in flight at a step's barrier: with 4 stages
+  // the copies of the step before (needed one step later), with 2 stages none
+  static constexpr int kPending = W == 8 ? 2 * kInstPerWave : 0;
   // V tile: segment permutation of row r (see the layout comment below)
   static constexpr int kSegs = kRowBytes / 64;        // 64-byte segments per row (4 or 2)
   static constexpr int kRowsPer256 = 256 / kRowBytes; // rows per sweep over all banks (1 or 2)
-  __device__ static __forceinline__ int vswz(int r) { return (r / kRowsPer256) & (kSegs - 1); }
+  __device__ __host__ static constexpr int vswz(int r) { return (r / kRowsPer256) & (kSegs - 1); }
   static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
 };
 
@@ -120,12 +143,28 @@ __device__ __forceinline__ i32x4 make_raw_buffer(const void* base, unsigned byte
   r[3] = 0x00020000;  // 32-bit untyped data
   return r;
 }
-__device__ __forceinline__ void copy16_to_lds(const i32x4& rsrc, int voff, int soff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc),
-                 "s"(__builtin_amdgcn_readfirstlane(soff))
-               : "memory");
+// The LDS address is lds_base + LDS_CONST + IMM + 16 i and the global offset voff + soff + IMM:
+// the instruction's immediate offset IMM (< 4096) advances both sides.  lds_base and soff
+// are wave-uniform; LDS_CONST is a compile-time constant, added inside the statement so
+// that the compiler does not keep one precomputed address per (stage, piece) in a
+// scalar register.
+// SOFF_CONST is added to soff the same way (the V copies of a step address their tile
+// relative to the K tile of the same step).
+template <int LDS_CONST, int IMM, int SOFF_CONST>
+__device__ __forceinline__ void copy16_to_lds(const i32x4& rsrc, int voff, int soff, int lds_base) {
+  static_assert(IMM >= 0 && IMM < 4096, "12-bit immediate offset");
+  if constexpr (SOFF_CONST == 0) {
+    asm volatile("s_add_u32 m0, %0, %c4\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen offset:%c5 lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff), "n"(LDS_CONST), "n"(IMM)
+                 : "memory", "scc");
+  } else {
+    int tmp;
+    asm volatile("s_add_u32 m0, %1, %c5\n\ts_add_i32 %0, %4, %c7\n\tbuffer_load_dwordx4 %2, %3, %0 offen offset:%c6 lds"
+                 : "=&s"(tmp)
+                 : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff), "n"(LDS_CONST), "n"(IMM), "n"(SOFF_CONST)
+                 : "memory", "scc");
+  }
 }
 template <int N>
 __device__ __forceinline__ void wait_copies_but() {  // all but the N most recent copies are complete
@@ -133,57 +172,75 @@ __device__ __forceinline__ void wait_copies_but() {  // all but the N most recen
   __builtin_amdgcn_s_waitcnt(0x0F70 | N);
 }
 
-// LDS layout of a K or V tile: row r (one key) is kRowBytes long; its 16-byte chunks
-// are permuted by an XOR with the row index so that fragment reads spread over all
-// banks:
-//   K tile: chunk c of row r sits at chunk position c ^ (r & (chunks-1)); the MFMA
-//           A-operand read (consecutive lanes = consecutive rows, same c) is then
-//           conflict free.
+// LDS layout of a K or V tile.  Row r (one key, kRowBytes long) is row r % kPieceRows of
+// piece r / kPieceRows; a piece is 1 KB, contiguous (the global -> LDS copy writes it with
+// one instruction), and pieces are kPieceStride bytes apart.  Inside a row the 16-byte
+// chunks are permuted so that fragment reads spread over all 64 banks (256 B):
+//   K tile, d = 128: chunk c of row r sits at chunk position c ^ (r & 3) (only the two
+//           low bits are permuted), and pieces are 1024 + 64 bytes apart.  The MFMA
+//           A-operand read (16 consecutive lanes = 16 consecutive rows = 4 pieces x 4 rows,
+//           same c) then touches 64-byte bank group (piece + c / 4) mod 4 and, inside it,
+//           chunk (c ^ row) & 3: 16 different 16-byte bank groups, conflict free.  Because
+//           only two chunk bits depend on the lane, the address of fragment (st, kb) is one
+//           of TWO per-lane registers (st even / odd) plus an immediate.
+//   K tile, d = 64:  chunk c of row r at chunk position c ^ (r & 7), pieces adjacent; one
+//           per-lane register per k-step.
 //   V tile: the 64-byte segment (c >> 2) sits at segment position (c >> 2) ^ vswz(r).  The
 //           transposing read takes 2 cycles of 32 lanes; in one cycle the lanes read 4
 //           consecutive rows x one 64-byte segment, and vswz spreads those 4 rows over the
 //           4 groups of 16 banks (measured: the 32-byte-pair permutation used before cost a
-//           2-way conflict on every transposing read).
-// Every fragment address is (per-lane base ^ constant), kept in a register, plus
-// stage offset + constant in the instruction's immediate.
-template <int D>
+//           2-way conflict on every transposing read).  Same pieces as the K tile.
+// Every fragment address is a per-lane base register plus stage offset + constant in
+// the instruction's immediate.
+template <class C>
 struct FragBase {
-  int k[FwdCfg<D>::kDSteps];   // K ring: lane base ^ (st << 5)
-  int v[FwdCfg<D>::kDBlocks];  // V ring: (lane base ^ (db << 6)) + offset of the V ring
+  int k[C::kKRegs];    // K ring
+  int v[C::kDBlocks];  // V ring: (lane base ^ (db << 6)) + offset of the V ring
   __device__ __forceinline__ void init(int lane, int smem_addr) {
-    using C = FwdCfg<D>;
     const int l32 = lane & 31, hi = lane >> 5;
     // K fragment (st, kb): row kb*32 + l32, logical chunk 2*st + hi
-    const int kbase = l32 * C::kRowBytes + (((l32 & (C::kChunks - 1)) ^ hi) << 4);
+    if constexpr (C::kD == 128) {
+      const int j = l32 & 3;
+      const int kbase = (l32 >> 2) * C::kKPieceStride + j * C::kRowBytes;
 #pragma unroll
-    for (int st = 0; st < C::kDSteps; ++st) k[st] = smem_addr + (kbase ^ (st << 5));
+      for (int e = 0; e < 2; ++e) k[e] = smem_addr + kbase + ((((e << 1) | hi) ^ j) << 4);
+    } else {
+      const int kbase = l32 * C::kRowBytes + (((l32 & (C::kChunks - 1)) ^ hi) << 4);
+#pragma unroll
+      for (int st = 0; st < C::kDSteps; ++st) k[st] = smem_addr + (kbase ^ (st << 5));
+    }
     // V fragment (ks, db): transposing read, see read_vfrag
     const int r8 = hi * 4 + ((lane & 15) >> 2);  // row inside the 16-key group (first read)
     const int grp = (lane >> 4) & 1;             // which 16 channels of the 32-channel block
-    const int vbase = r8 * C::kRowBytes + (C::vswz(r8) << 6) + grp * 32 + (lane & 3) * 8;
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db) v[db] = smem_addr + C::kVBase + (vbase ^ (db << 6));
+    for (int db = 0; db < C::kDBlocks; ++db) {
+      // (the XOR only touches bits 6..7 of the offset inside the piece)
+      const int in_piece = ((r8 % C::kPieceRows) * C::kRowBytes + grp * 32 + (lane & 3) * 8) ^
+                           ((C::vswz(r8) ^ db) << 6);
+      v[db] = smem_addr + C::kVBase + (r8 / C::kPieceRows) * C::kVPieceStride + in_piece;
+    }
   }
 };
 
 // K fragment F = st*2 + kb of the tile in ring stage KS: 32 keys x 16 channels; this
 // lane reads 8 channels of one key.
-template <int D, int KS, int F>
-__device__ __forceinline__ void read_kfrag(const FragBase<D>& fb) {
-  using C = FwdCfg<D>;
+template <class C, int KS, int F>
+__device__ __forceinline__ void read_kfrag(const FragBase<C>& fb) {
   constexpr int st = F >> 1, kb = F & 1;
-  read_k_slot<F % kSlots, KS * C::kTileBytes + kb * 32 * C::kRowBytes>(fb.k[st]);
+  constexpr int blk = KS * C::kKTileBytes + kb * (32 / C::kPieceRows) * C::kKPieceStride;
+  if constexpr (C::kD == 128) read_k_slot<F % kSlots, blk + (st >> 1) * 64>(fb.k[st & 1]);
+  else read_k_slot<F % kSlots, blk>(fb.k[st]);
 }
 // V^T fragment F = ks*kDBlocks + db of the tile in ring stage VS: 16 keys x 32 channels.
 // Transposing read: within 16 lanes, lane i supplies row (i/4), 8-byte piece (i%4)
 // of a 4-key x 16-channel block and receives channel i of the 4 keys.  MFMA k-slots
 // 0..7 (lanes < 32) are keys {0..3, 8..11} of the 16-key group and slots 8..15
 // (lanes >= 32) keys {4..7, 12..15}: how the S^T accumulators hold P^T.
-template <int D, int VS, int F>
-__device__ __forceinline__ void read_vfrag(const FragBase<D>& fb) {
-  using C = FwdCfg<D>;
+template <class C, int VS, int F>
+__device__ __forceinline__ void read_vfrag(const FragBase<C>& fb) {
   constexpr int ks = F / C::kDBlocks, db = F % C::kDBlocks;
-  read_v_slot<F % kSlots, VS * C::kTileBytes + ks * 16 * C::kRowBytes, 8 * C::kRowBytes>(fb.v[db]);
+  read_v_slot<F % kSlots, VS * C::kVTileBytes + ks * (16 / C::kPieceRows) * C::kVPieceStride,
+              8 / C::kPieceRows * C::kVPieceStride>(fb.v[db]);
 }
 
 // One wave's share of a 64-key x 32-query score tile (vector registers).
@@ -253,17 +310,17 @@ struct NoHook {
   template <class I>
   __device__ __forceinline__ void operator()(I) const {}
 };
-template <int D, int KS, int VSN, bool WITH_EXP, class Hook = NoHook>
+template <class C, int KS, int VSN, bool WITH_EXP, class Hook = NoHook>
 __device__ __forceinline__ void qk_phase(STile& nxt, const STile& cur, PTile& pcur, float mc,
-                                         float& l_run, float c2, const FragBase<D>& fb,
+                                         float& l_run, float c2, const FragBase<C>& fb,
                                          Hook hook = Hook{}) {
-  constexpr int NF = FwdCfg<D>::kNFK;
+  constexpr int NF = C::kNFK;
   static_for<NF>([&](auto F) {
     constexpr int f = decltype(F)::value;
     constexpr int st = f >> 1, kb = f & 1;
     constexpr int pf = f + kAhead;
-    if constexpr (pf < NF) read_kfrag<D, KS, (pf < NF ? pf : 0)>(fb);
-    else read_vfrag<D, VSN, (pf < NF ? 0 : pf - NF)>(fb);
+    if constexpr (pf < NF) read_kfrag<C, KS, (pf < NF ? pf : 0)>(fb);
+    else read_vfrag<C, VSN, (pf < NF ? 0 : pf - NF)>(fb);
     lds_wait<ops_after<f, NF, 1, 2>()>();
     mfma_s<f % kSlots, st, st == 0>(nxt.a[kb]);
     if constexpr (WITH_EXP) {
@@ -281,11 +338,17 @@ __device__ __forceinline__ void qk_phase(STile& nxt, const STile& cur, PTile& pc
 // the row max of the current score tile is taken between the MFMAs, starting after the
 // second one (see qk_phase).  MODE 2 (tail): exp2 of the current tile's first key block
 // (pairs 0..7) is spread between the MFMAs.
-template <int D, int VS, int KSN, int FIRST, int LAST, int MODE>
+// `before_k(...)` runs just before the first K fragment of stage KSN is requested (all V^T
+// fragments of this tile have been requested by then): where the 2-stage geometry awaits
+// the copies of that K tile and synchronises the workgroup.
+template <class C, int VS, int KSN, int FIRST, int LAST, int MODE, class BeforeK = NoHook>
 __device__ __forceinline__ void pv_phase(const PTile& pin, const STile& s, PTile& pout, float mc,
-                                         float& l_run, float& mx, float c2, const FragBase<D>& fb) {
-  constexpr int DB = FwdCfg<D>::kDBlocks;
-  constexpr int NF = FwdCfg<D>::kNFV;
+                                         float& l_run, float& mx, float c2, const FragBase<C>& fb,
+                                         BeforeK before_k = BeforeK{}) {
+  static_assert((FIRST <= C::kNFV - kAhead && LAST > C::kNFV - kAhead) || std::is_same<BeforeK, NoHook>::value,
+                "only the call that requests the first K fragment takes the hook");
+  constexpr int DB = C::kDBlocks;
+  constexpr int NF = C::kNFV;
   constexpr int NM = LAST - FIRST;  // MFMAs in this call
   float vmax[2];                    // MODE 1: two independent chains of partial maxima
   static_for<NM>([&](auto FI) {
@@ -294,8 +357,9 @@ __device__ __forceinline__ void pv_phase(const PTile& pin, const STile& s, PTile
     constexpr int ks = f / DB, db = f % DB;
     constexpr int kb = ks >> 1, hf = ks & 1;
     constexpr int pf = f + kAhead;
-    if constexpr (pf < NF) read_vfrag<D, VS, (pf < NF ? pf : 0)>(fb);
-    else read_kfrag<D, KSN, (pf < NF ? 0 : pf - NF)>(fb);
+    if constexpr (pf == NF) before_k(FI);
+    if constexpr (pf < NF) read_vfrag<C, VS, (pf < NF ? pf : 0)>(fb);
+    else read_kfrag<C, KSN, (pf < NF ? 0 : pf - NF)>(fb);
     lds_wait<ops_after<f, NF, 2, 1>()>();
     mfma_o<db, f % kSlots>(pin.a[kb][hf]);
     if constexpr (MODE == 1 && m >= 1) {
@@ -319,9 +383,10 @@ __device__ __forceinline__ void pv_phase(const PTile& pin, const STile& s, PTile
   if constexpr (MODE == 1) mx = pair_max(fmaxf(vmax[0], vmax[1]));
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
-  using C = FwdCfg<D>;
+template <int D, int W>
+__global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void moda_fwd_bf16_kernel(FwdParams p) {
+  using C = FwdCfg<D, W>;
+  constexpr int kThreads = C::kThreads, kBM = C::kBM, kStages = C::kStages;
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
   reserve_acc_registers();
 
@@ -367,34 +432,54 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   const int wave_last = p.causal ? min(nt - 1, qw0 / kBN) : nt - 1;
   const float c2 = p.scale_log2;
 
-  // ---- global -> LDS copies of one K or V tile.  One wave instruction moves 1 KB,
-  // so the chunk permutation is applied by choosing which global chunk each lane fetches.
-  int k_goff[C::kInstPerWave], v_goff[C::kInstPerWave];
-#pragma unroll
-  for (int i = 0; i < C::kInstPerWave; ++i) {
+  // ---- global -> LDS copies of one K or V tile.  One wave instruction moves one 1 KB
+  // piece, so the chunk permutation is applied by choosing which global chunk each lane
+  // fetches; it is the same for every piece (the permutations only look at the row index
+  // inside a piece), so one per-lane offset serves all K copies and one all V copies.
+  // A wave copies pieces wave * kInstPerWave + i, i < kInstPerWave, of every tile.
+  int k_goff, v_goff;
+  {
     const int lane = tid & 63;
-    const int r = (wave * C::kInstPerWave + i) * C::kRowsPerInst + lane / C::kChunks;
+    const int j = lane / C::kChunks;   // row inside the piece
     const int pc = lane % C::kChunks;  // chunk position this lane fills
-    const int kc = pc ^ (r & (C::kChunks - 1));
-    const int vc = (((pc >> 2) ^ C::vswz(r)) << 2) | (pc & 3);
-    k_goff[i] = r * C::kRowBytes + kc * 16;
-    v_goff[i] = r * C::kRowBytes + vc * 16;
+    const int kc = C::kD == 128 ? (pc ^ (j & 3)) : (pc ^ (j & (C::kChunks - 1)));
+    const int vc = (((pc >> 2) ^ C::vswz(j)) << 2) | (pc & 3);
+    k_goff = j * C::kRowBytes + kc * 16;
+    v_goff = j * C::kRowBytes + vc * 16;
   }
+  static_assert(C::vswz(0) == C::vswz(C::kPieceRows) && C::vswz(1) == C::vswz(1 + C::kPieceRows),
+                "the V permutation repeats from piece to piece");
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   const i32x4 k_buf = make_raw_buffer(Kb, (unsigned)T * C::kRowBytes);
   const i32x4 v_buf = make_raw_buffer(Vb, (unsigned)T * C::kRowBytes);
-  // copy instruction i (of kInstPerWave) of this wave's share of tile kt into ring byte offset stage_off
-  auto issue_one = [&](const i32x4& buf, int kt, int stage_off, const int (&goff)[C::kInstPerWave], int i) {
-    copy16_to_lds(buf, goff[i], kt * C::kTileBytes,
-                  smem_addr + stage_off + (wave * C::kInstPerWave + i) * C::kRowsPerInst * C::kRowBytes);
+  // Copy instruction I (of kInstPerWave) of this wave's share of tile kt into the ring stage at
+  // byte offset STAGE_OFF: piece wave * kInstPerWave + I.  The wave-dependent parts of both
+  // addresses are two scalars; everything else is a compile-time constant.
+  const int wave_lds = __builtin_amdgcn_readfirstlane((int)smem_addr + wave * C::kInstPerWave * C::kKPieceStride);
+  const int wave_lds_v = __builtin_amdgcn_readfirstlane((int)smem_addr + wave * C::kInstPerWave * C::kVPieceStride);
+  const int wave_goff = __builtin_amdgcn_readfirstlane(wave * C::kInstPerWave * 1024);
+  // `kt` is the K tile index of the step; the V tile copied in the same step is
+  // kStages - kVAhead tiles behind it.
+  auto issue_one = [&](auto IS_K, auto I, auto STAGE_OFF, const i32x4& buf, int kt) {
+    constexpr bool is_k = decltype(IS_K)::value;
+    constexpr int i = decltype(I)::value;
+    constexpr int stride = is_k ? C::kKPieceStride : C::kVPieceStride;
+    const int soff = __builtin_amdgcn_readfirstlane(kt * C::kGTileBytes) + wave_goff;
+    copy16_to_lds<decltype(STAGE_OFF)::value + i * (stride - 1024), i * 1024,
+                  is_k ? 0 : -(kStages - C::kVAhead) * C::kGTileBytes>(
+        buf, is_k ? k_goff : v_goff, soff, is_k ? wave_lds : wave_lds_v);
   };
-  auto issue_tile = [&](const i32x4& buf, int kt, int stage_off, const int (&goff)[C::kInstPerWave]) {
-#pragma unroll
-    for (int i = 0; i < C::kInstPerWave; ++i) issue_one(buf, kt, stage_off, goff, i);
+  auto issue_tile = [&](auto IS_K, auto STAGE_OFF, const i32x4& buf, int kt) {
+    static_for<C::kInstPerWave>([&](auto I) { issue_one(IS_K, I, STAGE_OFF, buf, kt); });
   };
-  // tile kt of K sits in K stage kt % 4, tile kt of V in V stage kt % 4 (tile -1: stage 3)
-  auto k_stage_off = [&](int stage) { return stage * C::kTileBytes; };
-  auto v_stage_off = [&](int stage) { return C::kVBase + stage * C::kTileBytes; };
+  constexpr std::true_type kIsK{};
+  constexpr std::false_type kIsV{};
+  // tile kt of K sits in K stage kt % kStages, tile kt of V in V stage kt % kStages
+  // (tile -1: the last stage)
+  auto k_stage_off = [](auto STAGE) { return std::integral_constant<int, decltype(STAGE)::value * C::kKTileBytes>{}; };
+  auto v_stage_off = [](auto STAGE) {
+    return std::integral_constant<int, C::kVBase + decltype(STAGE)::value * C::kVTileBytes>{};
+  };
 
   auto mask_tile = [&](STile& s, int kt) {
     const int k0 = kt * kBN;
@@ -411,16 +496,18 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   };
   auto needs_mask = [&](int kt) { return (p.causal && kt * kBN + kBN - 1 > qw0) || (kt * kBN + kBN > T); };
 
-  FragBase<D> fb;
+  FragBase<C> fb;
   fb.init(tid & 63, (int)smem_addr);
   float mx = 0.f;
 
   // ---- prologue: fill the rings, zero the V stage that stands in for "tile -1"
   // (its P is zero too, but 0 * garbage could be NaN), S(0) = K(0) Q^T.
-  for (int j = 0; j < kStages; ++j) issue_tile(k_buf, j, k_stage_off(j), k_goff);
-  for (int j = 0; j < 2; ++j) issue_tile(v_buf, j, v_stage_off(j), v_goff);
-  for (int i = tid * 16; i < C::kTileBytes; i += kThreads * 16)
-    *(i32x4*)(smem + v_stage_off(kStages - 1) + i) = (i32x4){0, 0, 0, 0};
+  static_for<kStages>([&](auto J) { issue_tile(kIsK, k_stage_off(J), k_buf, decltype(J)::value); });
+  static_for<C::kVAhead>([&](auto J) {
+    issue_tile(kIsV, v_stage_off(J), v_buf, decltype(J)::value + kStages - C::kVAhead);
+  });
+  for (int i = tid * 16; i < C::kVTileBytes; i += kThreads * 16)
+    *(i32x4*)(smem + C::kVBase + (kStages - 1) * C::kVTileBytes + i) = (i32x4){0, 0, 0, 0};
   wait_copies_but<0>();
   __syncthreads();
 
@@ -429,8 +516,8 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   zero(pA);
   clear(pB);
   {
-    static_for<kAhead>([&](auto I) { read_kfrag<D, 0, decltype(I)::value>(fb); });
-    qk_phase<D, 0, kStages - 1, false>(sA, sA, pA, 0.f, l_run, c2, fb);
+    static_for<kAhead>([&](auto I) { read_kfrag<C, 0, decltype(I)::value>(fb); });
+    qk_phase<C, 0, kStages - 1, false>(sA, sA, pA, 0.f, l_run, c2, fb);
     MODA_PIN();
     MODA_NOP(15);
     if (wave_last == 0 && needs_mask(0)) mask_tile(sA, 0);
@@ -450,17 +537,33 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
   // rare path: the pending P V is finished first, then the accumulators are rescaled.
   auto step = [&](auto SI, int kt, STile& cur, STile& nxt, const PTile& pprev, PTile& pcur) {
     constexpr int S = decltype(SI)::value;
-    constexpr int VS_PREV = (S + 3) % kStages;  // V tile kt-1
-    constexpr int KS_NEXT = (S + 1) % kStages;  // K tile kt+1
-    constexpr int VS_CUR = S;                   // V tile kt
+    constexpr int VS_PREV = (S + kStages - 1) % kStages;  // V tile kt-1
+    constexpr int KS_NEXT = (S + 1) % kStages;            // K tile kt+1
+    constexpr int VS_CUR = S % kStages;                   // V tile kt
     constexpr int NFV = C::kNFV;
     constexpr int HEAD = C::kDBlocks;  // V fragments of the first 16 keys
+    // Await this wave's copies and synchronise the workgroup.  With 4 stages this stands
+    // between the two matrix phases.  With 2 stages K tile kt+1 was only requested in step
+    // kt-1, and its first fragments are read at the end of the first matrix phase: the
+    // synchronisation point moves to just before that read.  All V^T fragment reads of tile
+    // kt-1 have been issued by then (LDS serves requests in order, and a copy into that
+    // stage is only requested after the barrier, so it lands after them).
+    constexpr bool kEarlySync = kStages == 2;
+    auto sync_copies = [&]() {
+      if (kt < nt) {
+        wait_copies_but<C::kPending>();
+        __syncthreads();
+      }
+    };
+    auto before_k = [&](auto) {
+      if constexpr (kEarlySync) sync_copies();
+    };
     if (kt <= wave_last) {
-      pv_phase<D, VS_PREV, KS_NEXT, 0, HEAD, 1>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
+      pv_phase<C, VS_PREV, KS_NEXT, 0, HEAD, 1>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
       const bool raise = (mx - m_run) * c2 > 8.f;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) {
         // Rare path (always taken for the first tile, where m_run = -inf).
-        pv_phase<D, VS_PREV, KS_NEXT, HEAD, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
+        pv_phase<C, VS_PREV, KS_NEXT, HEAD, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb, before_k);
         MODA_PIN();
         MODA_NOP(15);  // every MFMA above has retired
         const float m_new = fmaxf(m_run, mx);
@@ -474,46 +577,53 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
         static_for<8>([&](auto Q) { exp_pair<decltype(Q)::value>(cur, pcur, mc, l_run, c2); });
       } else {
         const float mc = m_run * c2;
-        pv_phase<D, VS_PREV, KS_NEXT, HEAD, NFV, 2>(pprev, cur, pcur, mc, l_run, mx, c2, fb);
+        pv_phase<C, VS_PREV, KS_NEXT, HEAD, NFV, 2>(pprev, cur, pcur, mc, l_run, mx, c2, fb, before_k);
       }
       // (for this wave's last tile the next K tile is not needed; it is read and
       //  multiplied all the same, which keeps the loop body free of branches)
     } else if (kt == wave_last + 1) {
       // this wave's last tile: only its P V is left (the K fragments it requests are never used)
-      pv_phase<D, VS_PREV, KS_NEXT, 0, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb);
+      pv_phase<C, VS_PREV, KS_NEXT, 0, NFV, 0>(pprev, cur, pcur, 0.f, l_run, mx, c2, fb, before_k);
       clear(pcur);
     } else {
       clear(pcur);
+      if constexpr (kEarlySync) sync_copies();
     }
 
     // Every step issues the same number of copies (tiles past the end of the tensor are
     // out of range of the raw buffer: nothing is fetched), so "all but the newest
-    // 2*kInstPerWave copies have landed" always means: K tile kt+2 and V tile kt, which
-    // are read next, are complete.
-    const int kt_k = kt + kStages, kt_v = kt + 2;
-    const int so_k = k_stage_off(S), so_v = v_stage_off((S + 2) % kStages);
-    if (kt < nt) {
-      wait_copies_but<2 * C::kInstPerWave>();
-      __syncthreads();
-      // every wave is past the first half of step kt: K tile kt and V tile kt-2 are dead
-      if (kt > wave_last) {
-        issue_tile(k_buf, kt_k, so_k, k_goff);
-        issue_tile(v_buf, kt_v, so_v, v_goff);
-      }
+    // kPending copies have landed" always means: K tile kt+1 and V tile kt, which are
+    // read next, are complete (with 4 stages K tile kt+2 too: one step of slack).
+    // The stages written are those of K tile kt (its scores were taken in step kt-1) and,
+    // with 4 stages, of V tile kt-2, with 2 stages of V tile kt-1 (consumed in the first
+    // half of this step): every wave is past those reads once it has passed the barrier.
+    const int kt_k = kt + kStages;  // the V tile of this step is kt + kVAhead
+    constexpr auto so_k = k_stage_off(std::integral_constant<int, S % kStages>{});
+    constexpr auto so_v = v_stage_off(std::integral_constant<int, (S + C::kVAhead) % kStages>{});
+    if constexpr (!kEarlySync) sync_copies();
+    // every wave is past the reads of the stages that this step's copies overwrite
+    if (kt < nt && kt > wave_last) {
+      issue_tile(kIsK, so_k, k_buf, kt_k);
+      issue_tile(kIsV, so_v, v_buf, kt_k);
     }
 
     if (kt <= wave_last) {
       const float mc = m_run * c2;
-      // this step's copies ride along, one after every fourth MFMA
+      // this step's copies ride along, spread evenly over the MFMAs of the phase
       auto hook = [&](auto M) {
         constexpr int m = decltype(M)::value;
-        if constexpr (m % 4 == 1 && m / 4 < 2 * C::kInstPerWave) {
-          constexpr int i = m / 4;
-          if constexpr (i < C::kInstPerWave) issue_one(k_buf, kt_k, so_k, k_goff, i);
-          else issue_one(v_buf, kt_v, so_v, v_goff, i - C::kInstPerWave);
+        constexpr int every = C::kNFK / (2 * C::kInstPerWave) >= 4 ? 4 : C::kNFK / (2 * C::kInstPerWave);
+        static_assert(every >= 1, "at most one copy per MFMA");
+        if constexpr (m % every == every / 2 && m / every < 2 * C::kInstPerWave) {
+          constexpr int i = m / every;
+          if constexpr (i < C::kInstPerWave)
+            issue_one(kIsK, std::integral_constant<int, i>{}, so_k, k_buf, kt_k);
+          else
+            issue_one(kIsV, std::integral_constant<int, (i < C::kInstPerWave ? 0 : i - C::kInstPerWave)>{}, so_v,
+                      v_buf, kt_k);
         }
       };
-      qk_phase<D, KS_NEXT, VS_CUR, true>(nxt, cur, pcur, mc, l_run, c2, fb, hook);
+      qk_phase<C, KS_NEXT, VS_CUR, true>(nxt, cur, pcur, mc, l_run, c2, fb, hook);
       if (kt + 1 == wave_last && needs_mask(kt + 1)) {
         MODA_PIN();
         MODA_NOP(15);
@@ -523,6 +633,7 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
       clear(nxt);
     }
   };
+  static_assert(kUnroll == 4, "the four steps below");
   for (int kt = 0; kt <= nt; kt += 4) {
     step(std::integral_constant<int, 0>{}, kt, sA, sB, pA, pB);
     if (kt + 1 <= nt) step(std::integral_constant<int, 1>{}, kt + 1, sB, sA, pB, pA);
@@ -714,16 +825,22 @@ __global__ __launch_bounds__(kThreads) void moda_fwd_bf16_kernel(FwdParams p) {
 
 namespace moda {
 
-int fwd_bf16_tile_rows() { return kBM; }
+int fwd_bf16_tile_rows(int waves) { return waves * kQPerWave; }
 
-hipError_t launch_fwd_bf16(const FwdParams& p, int d, hipStream_t stream) {
+hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t stream) {
   const long long blocks = (long long)p.B * p.Hq * p.n_qtiles;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  dim3 grid((unsigned)blocks), block(kThreads);
-  if (d == 128)
-    hipLaunchKernelGGL(moda_fwd_bf16_kernel<128>, grid, block, 0, stream, p);
+  if ((waves != 4 && waves != 8) || p.n_qtiles != (p.T + waves * kQPerWave - 1) / (waves * kQPerWave))
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks), block(waves * 64);
+  if (d == 128 && waves == 8)
+    hipLaunchKernelGGL((moda_fwd_bf16_kernel<128, 8>), grid, block, 0, stream, p);
+  else if (d == 128)
+    hipLaunchKernelGGL((moda_fwd_bf16_kernel<128, 4>), grid, block, 0, stream, p);
+  else if (d == 64 && waves == 8)
+    hipLaunchKernelGGL((moda_fwd_bf16_kernel<64, 8>), grid, block, 0, stream, p);
   else if (d == 64)
-    hipLaunchKernelGGL(moda_fwd_bf16_kernel<64>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL((moda_fwd_bf16_kernel<64, 4>), grid, block, 0, stream, p);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

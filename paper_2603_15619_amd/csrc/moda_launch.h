@@ -4,9 +4,10 @@
 
 namespace moda {
 
-// Rows of queries handled by one workgroup of the bf16 forward kernel.
-int fwd_bf16_tile_rows();
-hipError_t launch_fwd_bf16(const FwdParams& p, int d, hipStream_t stream);
+// bf16 forward kernel: `waves` (8 or 4) waves per workgroup, 32 queries each; p.n_qtiles
+// must be the number of such tiles in p.T.
+int fwd_bf16_tile_rows(int waves);
+hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t stream);
 hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream);
 
 // Backward (bf16, Hq == Hk): delta, dK/dV and dQ/depth kernels on `stream`.
