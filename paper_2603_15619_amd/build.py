@@ -29,15 +29,17 @@ def _compile(src):
 
 
 # Sources whose inline assembly owns ALL accumulation registers by name (see
-# csrc/moda_fwd_regs.h) up to the point where the kernel emits the marker comment
-# ACC_RELEASE_MARKER.  The compiler is not told that they hold live values, so the build
-# verifies on the generated assembly, per kernel and on its control-flow graph, that
-#   - no instruction that can execute before the marker touches an accumulation
+# csrc/moda_fwd_regs.h) between the points where the kernel emits the marker comments
+# ACC_ACQUIRE_MARKER and ACC_RELEASE_MARKER.  The compiler is not told that they hold live
+# values, so the build verifies on the generated assembly, per kernel and on its
+# control-flow graph, that
+#   - no instruction that can execute between the two markers touches an accumulation
 #     register unless it sits inside one of the hand-written assembly statements,
-#   - no hand-written statement that names an accumulation register can execute after
-#     the marker (from there on the registers are the compiler's),
+#   - no hand-written statement that names an accumulation register can execute before
+#     the acquire marker or after the release marker (there the registers are the compiler's),
 #   - nothing was spilled to scratch memory.
 NAMED_ACC_SOURCES = ("moda_fwd_bf16.hip",)
+ACC_ACQUIRE_MARKER = "MODA_ACC_REGISTERS_ACQUIRED"
 ACC_RELEASE_MARKER = "MODA_ACC_REGISTERS_RELEASED"
 
 
@@ -71,8 +73,8 @@ def _check_kernel(asm_path, name, body) -> None:
         if "#ASMEND" in line:
             in_asm = False
             continue
-        if in_asm and ACC_RELEASE_MARKER in line:
-            ins.append((n, ACC_RELEASE_MARKER, True))
+        if in_asm and (ACC_RELEASE_MARKER in line or ACC_ACQUIRE_MARKER in line):
+            ins.append((n, ACC_RELEASE_MARKER if ACC_RELEASE_MARKER in line else ACC_ACQUIRE_MARKER, True))
             continue
         code = line.split(";")[0].strip()
         if not code:
@@ -84,11 +86,13 @@ def _check_kernel(asm_path, name, body) -> None:
         if code.startswith("."):
             continue
         ins.append((n, code, in_asm))
-    markers = [i for i, x in enumerate(ins) if x[1] == ACC_RELEASE_MARKER]
-    if len(markers) != 1:
-        raise RuntimeError("%s: %s: expected exactly one %s, found %d"
-                           % (asm_path, name, ACC_RELEASE_MARKER, len(markers)))
-    marker = markers[0]
+    def the_marker(text):
+        found = [i for i, x in enumerate(ins) if x[1] == text]
+        if len(found) != 1:
+            raise RuntimeError("%s: %s: expected exactly one %s, found %d" % (asm_path, name, text, len(found)))
+        return found[0]
+
+    acquire, marker = the_marker(ACC_ACQUIRE_MARKER), the_marker(ACC_RELEASE_MARKER)
 
     def successors(i):
         op = ins[i][1].split()[0]
@@ -113,17 +117,20 @@ def _check_kernel(asm_path, name, body) -> None:
             todo.extend(successors(i))
         return seen
 
-    before = reach(0, stop=marker)          # can execute before the marker
-    after = reach(marker)                   # can execute after it
-    for i in sorted(before):
+    if marker in reach(0, stop=acquire):
+        raise RuntimeError("%s: %s: the release marker can be reached without passing the acquire marker"
+                           % (asm_path, name))
+    owned = reach(acquire, stop=marker)     # can execute between the markers
+    free = reach(0, stop=acquire) | reach(marker)  # before the acquire marker or after the release marker
+    for i in sorted(owned):
         n, code, hand = ins[i]
         if not hand and acc.search(code):
             raise RuntimeError("%s:%d: %s: compiler-allocated accumulation register while the named "
                                "ones are live: %s" % (asm_path, n, name, code))
-    for i in sorted(after):
+    for i in sorted(free):
         n, code, hand = ins[i]
         if hand and acc.search(code):
-            raise RuntimeError("%s:%d: %s: named accumulation register used after they were released: %s"
+            raise RuntimeError("%s:%d: %s: named accumulation register used outside the owned region: %s"
                                % (asm_path, n, name, code))
 
 

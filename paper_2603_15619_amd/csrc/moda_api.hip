@@ -27,15 +27,17 @@ moda_status check_shape(const moda_shape* s) {
   return MODA_OK;
 }
 
-// Geometry of the bf16 forward kernel (see moda_fwd_bf16.hip).  MODA_FWD_WAVES = 4 or 8
-// overrides the choice (for experiments).
+// Geometry of the bf16 forward kernel (see moda_fwd_bf16.hip): 8 waves (256 queries) per
+// workgroup, one workgroup per compute unit, unless that grid would leave compute units
+// without work: then 4 waves (128 queries), two workgroups per unit, twice as many
+// workgroups.  MODA_FWD_WAVES = 4 or 8 overrides the choice (for experiments).
 int fwd_waves_per_workgroup(const moda_shape* s) {
   if (const char* e = getenv("MODA_FWD_WAVES")) {
     const int w = atoi(e);
     if (w == 4 || w == 8) return w;
   }
-  (void)s;
-  return 8;
+  const long long tiles8 = (long long)s->B * s->Hq * ((s->T + 255) / 256);
+  return tiles8 < 256 ? 4 : 8;
 }
 
 float resolve_scale(const moda_shape* s) {

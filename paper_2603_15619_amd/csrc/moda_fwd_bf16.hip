@@ -410,6 +410,208 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const char* Kb = (const char*)p.Kseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
   const char* Vb = (const char*)p.Vseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
 
+  const int L = p.depth_count;
+  const float c2 = p.scale_log2;
+
+  // ---- The depth slots of the tile's own positions, folded into the running (m, l, o) of
+  // every query row, in a row-major mapping: d/8 lanes x 8 channels per row, 64 / (d/8) rows
+  // per wave step.  Three uses:
+  //   kDepthLast  (after the key loop): rows start from the exchange buffer (the key loop's
+  //               state), are folded with the depth slots, normalised and stored;
+  //   kDepthFirst (before the key loop): rows start empty, are folded with the depth slots
+  //               and written to the exchange buffer, from where the key loop picks them up;
+  //   kPlainStore: no depth slots (or already folded in): rows from the exchange buffer are
+  //               normalised and stored.
+  // Work items (row step, chunk of kDepthChunk slots) are walked in order with the loads of
+  // the next TWO items in flight while the current item is folded: the phase is bound by
+  // memory latency, i.e. by the bytes a compute unit keeps in flight, and the 128
+  // accumulation registers that the key loop does not need at that time hold most of them.
+  constexpr std::integral_constant<int, 0> kDepthLast{};
+  constexpr std::integral_constant<int, 1> kDepthFirst{};
+  constexpr std::integral_constant<int, 2> kPlainStore{};
+  auto depth_phase = [&](auto MODE_T) {
+    constexpr int MODE = decltype(MODE_T)::value;
+    const int lane = lane_id();
+    unsigned char* xw = smem + wave * C::kXWave;
+    float* ml = (float*)(xw + 32 * C::kXRow);
+    constexpr int LPR = C::kChunks;   // lanes per query row: each owns 8 channels (16 B)
+    constexpr int RPS = 64 / LPR;     // query rows per wave step
+    constexpr int NIT = 32 / RPS;     // row steps of the wave's 32 queries
+    const int rg = lane / LPR;
+    const int l16 = lane % LPR;       // owns channels 8*l16 .. 8*l16+7
+    const size_t drow = (size_t)p.depth_alloc * C::kRowBytes;  // bytes of one position's slots
+    const char* Kdb = (const char*)p.Kdepth + (size_t)(b * p.Hk + g) * T * drow;
+    const char* Vdb = (const char*)p.Vdepth + (size_t)(b * p.Hk + g) * T * drow;
+    char* Ob = (char*)p.O + (size_t)bh * T * C::kRowBytes;
+    float* LSEb = p.LSE + (size_t)bh * T;
+
+    // row state in the row-major mapping
+    float o[8], m = 0.f, l = 1.f;
+    auto begin_row = [&](int row) {
+      if constexpr (MODE == 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] = 0.f;
+        m = -INFINITY;
+        l = 0.f;
+      } else {
+        const f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
+        const f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
+        o[0] = o0[0]; o[1] = o0[1]; o[2] = o0[2]; o[3] = o0[3];
+        o[4] = o1[0]; o[5] = o1[1]; o[6] = o1[2]; o[7] = o1[3];
+        m = ml[2 * row];
+        l = ml[2 * row + 1];
+      }
+    };
+    auto end_row = [&](int row) {
+      if constexpr (MODE == 1) {
+        *(f32x4*)(xw + row * C::kXRow + l16 * 32) = (f32x4){o[0], o[1], o[2], o[3]};
+        *(f32x4*)(xw + row * C::kXRow + l16 * 32 + 16) = (f32x4){o[4], o[5], o[6], o[7]};
+        if (l16 == 0) {
+          ml[2 * row] = m;
+          ml[2 * row + 1] = l;
+        }
+      } else {
+        const int t = qw0 + row;
+        if (t < T) {
+          const float inv = 1.0f / l;
+          u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
+                      pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
+          *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
+          if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
+        }
+      }
+    };
+    if constexpr (MODE == 2) {
+      for (int it = 0; it < NIT; ++it) {
+        const int row = it * RPS + rg;
+        begin_row(row);
+        end_row(row);
+      }
+      return;
+    }
+
+    struct DepthBuf {
+      u32x4 q;
+      u32x4 k[kDepthChunk], v[kDepthChunk];
+    };
+    const int nch = (L + kDepthChunk - 1) / kDepthChunk;
+    // The depth slabs are read through bounds-checked raw buffers with 32-bit offsets:
+    // a chunk's slots past depth_alloc at the very end of the slab read as zero, and no
+    // index clamping is needed (slots past depth_count get weight zero below).
+    const size_t slab_bytes = (size_t)T * drow;
+    const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)Vdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
+    auto issue = [&](int it, int c, DepthBuf& buf) {
+      const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
+      buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
+      const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+      const int soff = c * kDepthChunk * C::kRowBytes;
+#pragma unroll
+      for (int i = 0; i < kDepthChunk; ++i)
+        buf.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+#pragma unroll
+      for (int i = 0; i < kDepthChunk; ++i)
+        buf.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+    };
+    auto fold = [&](int c, const DepthBuf& buf) {
+      float sc[kDepthChunk];
+      float mx2 = m;
+#pragma unroll
+      for (int i = 0; i < kDepthChunk; ++i) {
+        float a = dot2_bf16(buf.q[0], buf.k[i][0], 0.f);
+        a = dot2_bf16(buf.q[1], buf.k[i][1], a);
+        a = dot2_bf16(buf.q[2], buf.k[i][2], a);
+        a = dot2_bf16(buf.q[3], buf.k[i][3], a);
+        a = group_sum<LPR>(a);
+        sc[i] = (c * kDepthChunk + i < L) ? a : -INFINITY;
+        mx2 = fmaxf(mx2, sc[i]);
+      }
+      // (a chunk always holds at least one attended slot, so mx2 is finite; with m = -inf,
+      //  the state of an empty row, the factor is exp2(-inf) = 0)
+      const float al = fast_exp2((m - mx2) * c2);
+      const float mc = mx2 * c2;
+      m = mx2;
+      l *= al;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) o[k] *= al;
+#pragma unroll
+      for (int i = 0; i < kDepthChunk; ++i) {
+        const float pw = fast_exp2(sc[i] * c2 - mc);
+        l += pw;
+        // weight rounded to bf16 (as P is for the sequence keys) and placed in the low or
+        // the high half of a pair: one packed dot product per output channel
+        const uint32_t w_lo = pack_bf16(pw, 0.f);
+        const uint32_t w_hi = w_lo << 16;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          o[2 * k] = dot2_bf16(w_lo, buf.v[i][k], o[2 * k]);
+          o[2 * k + 1] = dot2_bf16(w_hi, buf.v[i][k], o[2 * k + 1]);
+        }
+      }
+    };
+    // Item cursors: (it, c) is the item being folded, (iti, ci) the next one whose loads
+    // are to be issued (two items ahead).  Past the end the issue cursor stays on the last
+    // item (its loads are repeated and ignored): a conditional issue would make the
+    // compiler wait for the older loads as if the newer ones were not there.
+    int it = 0, c = 0;
+    int iti = 0, ci = 0;
+    auto advance = [&](int& i_, int& c_) {
+      if (++c_ == nch) {
+        c_ = 0;
+        ++i_;
+      }
+    };
+    auto issue_next = [&](DepthBuf& buf) {
+      issue(iti, ci, buf);
+      int i2 = iti, c2n = ci;
+      advance(i2, c2n);
+      if (i2 < NIT) {
+        iti = i2;
+        ci = c2n;
+      }
+      MODA_PIN();  // these loads are issued before anything below waits for older ones
+    };
+    // fold the current item from `cur`; false when it was the last one
+    auto one = [&](const DepthBuf& cur, DepthBuf& refill) -> bool {
+      issue_next(refill);
+      const int row = it * RPS + rg;
+      if (c == 0) begin_row(row);
+      fold(c, cur);
+      if (c == nch - 1) end_row(row);
+      advance(it, c);
+      return it < NIT;
+    };
+    DepthBuf bufA, bufB, bufC;
+    issue_next(bufA);
+    issue_next(bufB);
+    while (true) {
+      if (!one(bufA, bufC)) break;
+      if (!one(bufB, bufA)) break;
+      if (!one(bufC, bufB)) break;
+    }
+  };
+
+  // ---- Which end of the kernel takes the depth slots.  The depth phase leaves the matrix
+  // pipe idle and is bound by what ONE compute unit can pull from HBM (about 50 GB/s
+  // measured, where the chip's 8 TB/s shared by all 256 units would be about 30 GB/s each).
+  // When every workgroup streams its depth slots after its key loop, the compute units
+  // of a short-sequence launch all stream at the same time, at the shared rate, and all
+  // compute at the same time, with HBM idle.  Every other workgroup therefore takes its
+  // depth slots FIRST: half of the units stream, at the full per-unit rate, while the other
+  // half computes.  The result does not depend on the order (one softmax over the union).
+  // Workgroup ids are dealt round-robin to the 8 dies: the role alternates within a die.
+  const bool depth_first = L > 0 && ((blockIdx.x >> 3) & 1) != 0;
+  if (depth_first) {
+    depth_phase(kDepthFirst);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  // From here to the release marker the accumulation registers are owned by name.
+  asm volatile("; MODA_ACC_REGISTERS_ACQUIRED" ::: "memory");
+
   // ---- Q fragments (MFMA B operand of S^T = K Q^T), resident in accumulation registers
   {
     i32x4 qtmp[C::kDSteps];  // all loads are issued before the first one is consumed
@@ -421,16 +623,38 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     MODA_PIN();
     static_for<C::kDSteps>([&](auto ST) { set_q<decltype(ST)::value>(qtmp[decltype(ST)::value]); });
   }
-  static_for<C::kDBlocks * 16>([&](auto R) { zero_acc<kAccO + decltype(R)::value>(); });
-
   float m_run = -INFINITY;  // reference max of the raw scores <q,k>
   float l_run = 0.f;        // this lane's share of the normaliser
+  if (depth_first) {
+    // state left by the depth slots, from the row-major exchange buffer into the accumulator
+    // layout (the inverse of the epilogue's exchange); the lane pair (l, l ^ 32) shares a row:
+    // both hold its reference max, one of them its normaliser
+    const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
+    const unsigned char* xw = smem + wave * C::kXWave;
+    const float* ml = (const float*)(xw + 32 * C::kXRow);
+    static_for<C::kDBlocks>([&](auto DBI) {
+      constexpr int db = decltype(DBI)::value;
+      static_for<4>([&](auto BQ) {
+        constexpr int bq = decltype(BQ)::value;
+        constexpr int r0 = kAccO + db * 16 + bq * 4;
+        const f32x4 v = *(const f32x4*)(xw + l32 * C::kXRow + (db * 32 + bq * 8 + hi * 4) * 4);
+        write_acc<r0>(v[0]);
+        write_acc<r0 + 1>(v[1]);
+        write_acc<r0 + 2>(v[2]);
+        write_acc<r0 + 3>(v[3]);
+      });
+    });
+    m_run = ml[2 * l32];
+    l_run = hi == 0 ? ml[2 * l32 + 1] : 0.f;
+    __syncthreads();  // every wave has its state: the buffer becomes the K/V rings
+  } else {
+    static_for<C::kDBlocks * 16>([&](auto R) { zero_acc<kAccO + decltype(R)::value>(); });
+  }
 
   // number of key tiles this workgroup walks, and the last one this wave needs
   const int n_keys = p.causal ? min(T, q0 + kBM) : T;
   const int nt = (n_keys + kBN - 1) / kBN;
   const int wave_last = p.causal ? min(nt - 1, qw0 / kBN) : nt - 1;
-  const float c2 = p.scale_log2;
 
   // ---- global -> LDS copies of one K or V tile.  One wave instruction moves one 1 KB
   // piece, so the chunk permutation is applied by choosing which global chunk each lane
@@ -647,22 +871,11 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   __syncthreads();
 
   // ================= epilogue: accumulator layout -> row-major, depth slots, store
-  const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
-  unsigned char* xw = smem + wave * C::kXWave;
-  float* ml = (float*)(xw + 32 * C::kXRow);
-  constexpr int LPR = C::kChunks;   // lanes per query row: each owns 8 channels (16 B)
-  constexpr int RPS = 64 / LPR;     // query rows per wave step
-  const int rg = lane / LPR;
-  const int l16 = lane % LPR;       // owns channels 8*l16 .. 8*l16+7
-  const int L = p.depth_count;
-  const size_t drow = (size_t)p.depth_alloc * C::kRowBytes;  // bytes of one position's slots
-  const char* Kdb = (const char*)p.Kdepth + (size_t)(b * p.Hk + g) * T * drow;
-  const char* Vdb = (const char*)p.Vdepth + (size_t)(b * p.Hk + g) * T * drow;
-  char* Ob = (char*)p.O + (size_t)bh * T * C::kRowBytes;
-  float* LSEb = p.LSE + (size_t)bh * T;
-
-  // accumulators -> this wave's exchange buffer, (m, l) per row
-  auto exchange = [&]() {
+  {
+    // accumulators -> this wave's exchange buffer, (m, l) per row
+    const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
+    unsigned char* xw = smem + wave * C::kXWave;
+    float* ml = (float*)(xw + 32 * C::kXRow);
     const float l_tot = pair_sum(l_run);
     static_for<C::kDBlocks>([&](auto DBI) {
       constexpr int db = decltype(DBI)::value;
@@ -680,145 +893,12 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  };
-  // row state in the row-major mapping
-  float o[8], m = 0.f, l = 1.f;
-  auto load_row = [&](int row) {
-    const f32x4 o0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
-    const f32x4 o1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
-    o[0] = o0[0]; o[1] = o0[1]; o[2] = o0[2]; o[3] = o0[3];
-    o[4] = o1[0]; o[5] = o1[1]; o[6] = o1[2]; o[7] = o1[3];
-    m = ml[2 * row];
-    l = ml[2 * row + 1];
-  };
-  auto store_row = [&](int t) {
-    if (t < T) {
-      const float inv = 1.0f / l;
-      u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
-                  pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
-      *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
-      if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
-    }
-  };
-  constexpr int NIT = 32 / RPS;  // row steps of the wave's 32 queries
-
-  exchange();
+  }
   // From here on the accumulation registers are the compiler's (it parks depth K/V
   // loads in them); the build step checks that on the generated code.
   asm volatile("; MODA_ACC_REGISTERS_RELEASED" ::: "memory");
-  if (L == 0) {
-    for (int it = 0; it < NIT; ++it) {
-      const int row = it * RPS + rg;
-      load_row(row);
-      store_row(qw0 + row);
-    }
-    return;
-  }
-
-  // ---- depth slots.  Work items (row step, chunk of kDepthChunk slots) are walked in
-  // order with the loads of the next TWO items in flight while the current item is
-  // folded into the row's (m, l, o): the phase is bound by memory latency, i.e. by the
-  // bytes a compute unit keeps in flight, and the 128 accumulation registers that the
-  // key loop no longer needs hold most of them.
-  struct DepthBuf {
-    u32x4 q;
-    u32x4 k[kDepthChunk], v[kDepthChunk];
-  };
-  const int nch = (L + kDepthChunk - 1) / kDepthChunk;
-  // The depth slabs are read through bounds-checked raw buffers with 32-bit offsets:
-  // a chunk's slots past depth_alloc at the very end of the slab read as zero, and no
-  // index clamping is needed (slots past depth_count get weight zero below).
-  const size_t slab_bytes = (size_t)T * drow;
-  const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)Vdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
-  auto issue = [&](int it, int c, DepthBuf& buf) {
-    const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
-    buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
-    const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
-    const int soff = c * kDepthChunk * C::kRowBytes;
-#pragma unroll
-    for (int i = 0; i < kDepthChunk; ++i)
-      buf.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
-#pragma unroll
-    for (int i = 0; i < kDepthChunk; ++i)
-      buf.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
-  };
-  auto fold = [&](int c, const DepthBuf& buf) {
-    float sc[kDepthChunk];
-    float mx2 = m;
-#pragma unroll
-    for (int i = 0; i < kDepthChunk; ++i) {
-      float a = dot2_bf16(buf.q[0], buf.k[i][0], 0.f);
-      a = dot2_bf16(buf.q[1], buf.k[i][1], a);
-      a = dot2_bf16(buf.q[2], buf.k[i][2], a);
-      a = dot2_bf16(buf.q[3], buf.k[i][3], a);
-      a = group_sum<LPR>(a);
-      sc[i] = (c * kDepthChunk + i < L) ? a : -INFINITY;
-      mx2 = fmaxf(mx2, sc[i]);
-    }
-    const float al = fast_exp2((m - mx2) * c2);
-    const float mc = mx2 * c2;
-    m = mx2;
-    l *= al;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) o[k] *= al;
-#pragma unroll
-    for (int i = 0; i < kDepthChunk; ++i) {
-      const float pw = fast_exp2(sc[i] * c2 - mc);
-      l += pw;
-      // weight rounded to bf16 (as P is for the sequence keys) and placed in the low or
-      // the high half of a pair: one packed dot product per output channel
-      const uint32_t w_lo = pack_bf16(pw, 0.f);
-      const uint32_t w_hi = w_lo << 16;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        o[2 * k] = dot2_bf16(w_lo, buf.v[i][k], o[2 * k]);
-        o[2 * k + 1] = dot2_bf16(w_hi, buf.v[i][k], o[2 * k + 1]);
-      }
-    }
-  };
-  // Item cursors: (it, c) is the item being folded, (iti, ci) the next one whose loads
-  // are to be issued (two items ahead).  Past the end the issue cursor stays on the last
-  // item (its loads are repeated and ignored): a conditional issue would make the
-  // compiler wait for the older loads as if the newer ones were not there.
-  int it = 0, c = 0;
-  int iti = 0, ci = 0;
-  auto advance = [&](int& i_, int& c_) {
-    if (++c_ == nch) {
-      c_ = 0;
-      ++i_;
-    }
-  };
-  auto issue_next = [&](DepthBuf& buf) {
-    issue(iti, ci, buf);
-    int i2 = iti, c2n = ci;
-    advance(i2, c2n);
-    if (i2 < NIT) {
-      iti = i2;
-      ci = c2n;
-    }
-    MODA_PIN();  // these loads are issued before anything below waits for older ones
-  };
-  // fold the current item from `cur`; false when it was the last one
-  auto one = [&](const DepthBuf& cur, DepthBuf& refill) -> bool {
-    issue_next(refill);
-    const int row = it * RPS + rg;
-    if (c == 0) load_row(row);
-    fold(c, cur);
-    if (c == nch - 1) store_row(qw0 + row);
-    advance(it, c);
-    return it < NIT;
-  };
-  DepthBuf bufA, bufB, bufC;
-  issue_next(bufA);
-  issue_next(bufB);
-  while (true) {
-    if (!one(bufA, bufC)) break;
-    if (!one(bufB, bufA)) break;
-    if (!one(bufC, bufB)) break;
-  }
+  if (L == 0 || depth_first) depth_phase(kPlainStore);
+  else depth_phase(kDepthLast);
 }
 
 }  // namespace moda

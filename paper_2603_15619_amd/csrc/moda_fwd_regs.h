@@ -99,6 +99,10 @@ __device__ __forceinline__ void zero_acc() {
   asm volatile("v_accvgpr_write_b32 a%c0, 0" : : "n"(R));
 }
 template <int R>
+__device__ __forceinline__ void write_acc(float x) {
+  asm volatile("v_accvgpr_write_b32 a%c1, %0" : : "v"(x), "n"(R));
+}
+template <int R>
 __device__ __forceinline__ void scale_acc(float f) {
   float t;
   asm volatile("v_accvgpr_read_b32 %0, a%c2\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a%c2, %0"

@@ -74,6 +74,17 @@ def test_bf16_shapes(T, d, L):
     check_full(1, 2, 2, T, d, L, "bf16", 100 + T + L)
 
 
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("T,d,L", [(1500, 128, 15), (1100, 64, 6), (129, 128, 2), (2048, 128, 0)])
+def test_bf16_both_geometries(monkeypatch, waves, T, d, L):
+    """The bf16 kernel has two workgroup geometries (8 waves with 4-stage K/V rings, 4 waves
+    with 2-stage rings), normally chosen from the grid size; here each is forced on shapes
+    that span many key tiles, so that every ring stage is reused several times, and both
+    orders of the depth phase (before / after the key loop) occur."""
+    monkeypatch.setenv("MODA_FWD_WAVES", str(waves))
+    check_full(2, 4, 2, T, d, L, "bf16", 400 + T + waves)
+
+
 @pytest.mark.parametrize("T,d,L", [(300, 128, 5), (130, 64, 17), (1, 64, 2)])
 def test_f32_shapes(T, d, L):
     check_full(2, 2, 2, T, d, L, "f32", 200 + T)
