@@ -18,6 +18,8 @@
 //            query's own position give dKdepth, dVdepth (row-local, written once)
 //            and their share of dQ.
 // Grouped-query attention (Hq != Hk) is not handled here.
+#include <type_traits>
+
 #include "moda_launch.h"
 #include "moda_tile.h"
 
@@ -144,41 +146,38 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
       for (int st = 0; st < Tl::kDSteps; ++st) {
         s = mfma_bf16(Tl::row_frag(qtile, qb, st, lane), kf[st], s);
         dp = mfma_bf16(Tl::row_frag(dotile, qb, st, lane), vf[st], dp);
+        // (fragment reads are not hoisted across this point: with all of a tile's reads
+        //  issued up front the kernel runs out of registers and spills K / V fragments)
+        if (st == Tl::kDSteps - 1) __builtin_amdgcn_sched_barrier(0);
       }
-      bf16x8 pb[2], dsb[2];  // [16-query half]
-      float pv[16], dsv[16];
-#pragma unroll
-      for (int b4 = 0; b4 < 4; ++b4) {
-        const f32x4 l4 = *(const f32x4*)(lse_s + qb * 32 + b4 * 8 + hi * 4);
-        const f32x4 d4 = *(const f32x4*)(del_s + qb * 32 + b4 * 8 + hi * 4);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int i = b4 * 4 + r;
-          const int q = q0 + qb * 32 + b4 * 8 + hi * 4 + r;
-          const bool vis = q < T && (!p.causal || key <= q);
-          const float pe = vis ? fast_exp2(s[i] * c2 - l4[r]) : 0.f;
-          pv[i] = pe;
-          dsv[i] = pe * (dp[i] - d4[r]);
-        }
-      }
+      // one 16-query half at a time: P and dS packed to bf16, then straight into the products
+      // that contract over those 16 queries (keeps few temporaries alive)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        float a[8], b[8];
+        float pv[8], dsv[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          a[k] = pv[hf * 8 + k];
-          b[k] = dsv[hf * 8 + k];
+        for (int b2 = 0; b2 < 2; ++b2) {
+          const int b4 = hf * 2 + b2;
+          const f32x4 l4 = *(const f32x4*)(lse_s + qb * 32 + b4 * 8 + hi * 4);
+          const f32x4 d4 = *(const f32x4*)(del_s + qb * 32 + b4 * 8 + hi * 4);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i = b4 * 4 + r;
+            const int q = q0 + qb * 32 + b4 * 8 + hi * 4 + r;
+            const bool vis = q < T && (!p.causal || key <= q);
+            const float pe = vis ? fast_exp2(s[i] * c2 - l4[r]) : 0.f;
+            pv[b2 * 4 + r] = pe;
+            dsv[b2 * 4 + r] = pe * (dp[i] - d4[r]);
+          }
         }
-        pb[hf] = pack8(a);
-        dsb[hf] = pack8(b);
-      }
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
+        const bf16x8 pb = pack8(pv), dsb = pack8(dsv);
 #pragma unroll
         for (int db = 0; db < Tl::kDBlocks; ++db) {
-          dv[db] = mfma_bf16(Tl::tr_frag(dotile, qb * 2 + hf, db, lane), pb[hf], dv[db]);
-          dk[db] = mfma_bf16(Tl::tr_frag(qtile, qb * 2 + hf, db, lane), dsb[hf], dk[db]);
+          dv[db] = mfma_bf16(Tl::tr_frag(dotile, qb * 2 + hf, db, lane), pb, dv[db]);
+          dk[db] = mfma_bf16(Tl::tr_frag(qtile, qb * 2 + hf, db, lane), dsb, dk[db]);
+
         }
+      }
     }
   }
   __syncthreads();
@@ -258,17 +257,223 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const float lse2 = LSEb[qrow] * kLog2e;
   const float delta = Db[qrow];
 
+  const float c2 = p.scale_log2;
+  unsigned char* xw = smem + wave * C::kXWave;  // this wave's fp32 exchange buffer (overlaps the ring)
+  constexpr int LPR = Tl::kChunks, RPS = 64 / LPR, NIT = 32 / RPS;
+  const int L = p.depth_count, La = p.depth_alloc;
+
+  // ---- Depth slots of the tile's own positions, row-major mapping (d/8 lanes x 8 channels per
+  // query row, 64 / (d/8) rows per wave step): dKdepth, dVdepth (row-local, written once) and
+  // the depth share of dQ.  MODE 0 (after the key loop): a row starts from the exchange
+  // buffer (the key loop's dQ), adds its depth share and is stored.  MODE 1 (before the key
+  // loop): a row starts from zero and leaves its depth share in the exchange buffer, from
+  // where the key loop picks it up.  Work items (row step, chunk of kChunk slots) are walked
+  // with the loads of the next two items in flight (the phase is bound by memory latency).
+  constexpr int kChunk = 5;
+  auto depth_grad = [&](auto MODE_T) {
+    constexpr int MODE = decltype(MODE_T)::value;
+    const int rg = lane / LPR, l16 = lane % LPR;
+    const size_t drow = (size_t)La * Tl::kRowBytes;
+    const size_t slab = (size_t)T * drow;
+    const char* Kdb = (const char*)p.Kdepth + (size_t)bh * slab;
+    const char* Vdb = (const char*)p.Vdepth + (size_t)bh * slab;
+    char* dKdb = (char*)p.dKdepth + (size_t)bh * slab;
+    char* dVdb = (char*)p.dVdepth + (size_t)bh * slab;
+    char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
+    // bounds-checked raw buffers: slots of a chunk past the end of the slab read as zero
+    // (slots past depth_count or depth_alloc are masked below)
+    const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Kdb, 0, (int)(unsigned)slab, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Vdb, 0, (int)(unsigned)slab, 0x00020000);
+    const __amdgpu_buffer_rsrc_t dkd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dKdb, 0, (int)(unsigned)slab, 0x00020000);
+    const __amdgpu_buffer_rsrc_t dvd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dVdb, 0, (int)(unsigned)slab, 0x00020000);
+    const int nch = (L + kChunk - 1) / kChunk;
+
+    struct Item {
+      u32x4 q, g;   // the row's Q and dO channels of this lane
+      float l2, dl;  // LSE * log2(e), delta
+      u32x4 k[kChunk], v[kChunk];
+    };
+    float acc[8];
+    auto begin_row = [&](int row) {
+      if constexpr (MODE == 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+      } else {
+        const f32x4 a0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
+        const f32x4 a1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
+        acc[0] = a0[0]; acc[1] = a0[1]; acc[2] = a0[2]; acc[3] = a0[3];
+        acc[4] = a1[0]; acc[5] = a1[1]; acc[6] = a1[2]; acc[7] = a1[3];
+      }
+    };
+    auto end_row = [&](int row) {
+      if constexpr (MODE == 1) {
+        *(f32x4*)(xw + row * C::kXRow + l16 * 32) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+        *(f32x4*)(xw + row * C::kXRow + l16 * 32 + 16) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+      } else {
+        const int t = qw0 + row;
+        if (t < T) {
+          const float f = p.scale;
+          u32x4 ov = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f),
+                      pack_bf16(acc[4] * f, acc[5] * f), pack_bf16(acc[6] * f, acc[7] * f)};
+          *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
+        }
+      }
+    };
+    if (L == 0) {  // (MODE 0 only) no attended slots: dQ as it is, zero gradients for allocated slots
+      for (int it = 0; it < NIT; ++it) {
+        const int row = it * RPS + rg, t = qw0 + row;
+        begin_row(row);
+        end_row(row);
+        if (t < T) {
+          const u32x4 z = {0u, 0u, 0u, 0u};
+          for (int i = 0; i < La; ++i) {
+            *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+            *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          }
+        }
+      }
+      return;
+    }
+    auto issue = [&](int it, int c, Item& b) {
+      const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1; nothing of them is stored
+      b.q = *(const u32x4*)(Qb + (size_t)tc * Tl::kRowBytes + l16 * 16);
+      b.g = *(const u32x4*)(dOb + (size_t)tc * Tl::kRowBytes + l16 * 16);
+      b.l2 = LSEb[tc] * kLog2e;
+      b.dl = Db[tc];
+      const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+      const int soff = c * kChunk * Tl::kRowBytes;
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+        b.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * Tl::kRowBytes, soff, 2);
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+        b.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * Tl::kRowBytes, soff, 2);
+    };
+    auto fold = [&](int it, int c, const Item& b) {
+      const int t = qw0 + it * RPS + rg;
+      const bool live = t < T;  // rows past the end compute on row T-1 and store nothing
+      const int voff = (int)((unsigned)min(t, T - 1) * (unsigned)drow + (unsigned)l16 * 16u);
+      const int soff = c * kChunk * Tl::kRowBytes;
+      float qx[8], gx[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        qx[2 * k] = bf16_lo(b.q[k]);
+        qx[2 * k + 1] = bf16_hi(b.q[k]);
+        gx[2 * k] = bf16_lo(b.g[k]);
+        gx[2 * k + 1] = bf16_hi(b.g[k]);
+      }
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        float sdot = 0.f, gdot = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          sdot = dot2_bf16(b.q[k], b.k[i][k], sdot);
+          gdot = dot2_bf16(b.g[k], b.v[i][k], gdot);
+        }
+        sdot = group_sum<LPR>(sdot);
+        gdot = group_sum<LPR>(gdot);
+        const int slot = c * kChunk + i;
+        if (slot < La) {  // uniform
+          // slots past depth_count: weight zero, so zero gradients are written
+          const float pe = slot < L ? fast_exp2(sdot * c2 - b.l2) : 0.f;
+          const float e = pe * (gdot - b.dl);
+          const float es = e * p.scale;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            acc[2 * k] += e * bf16_lo(b.k[i][k]);
+            acc[2 * k + 1] += e * bf16_hi(b.k[i][k]);
+          }
+          const u32x4 o1 = {pack_bf16(pe * gx[0], pe * gx[1]), pack_bf16(pe * gx[2], pe * gx[3]),
+                            pack_bf16(pe * gx[4], pe * gx[5]), pack_bf16(pe * gx[6], pe * gx[7])};
+          const u32x4 o2 = {pack_bf16(es * qx[0], es * qx[1]), pack_bf16(es * qx[2], es * qx[3]),
+                            pack_bf16(es * qx[4], es * qx[5]), pack_bf16(es * qx[6], es * qx[7])};
+          if (live) {
+            __builtin_amdgcn_raw_buffer_store_b128(o1, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
+            __builtin_amdgcn_raw_buffer_store_b128(o2, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
+          }
+        }
+      }
+    };
+    int it = 0, c = 0, iti = 0, ci = 0;
+    auto advance = [&](int& i_, int& c_) {
+      if (++c_ == nch) {
+        c_ = 0;
+        ++i_;
+      }
+    };
+    // (past the end the issue cursor stays on the last item: its loads are repeated and ignored)
+    auto issue_next = [&](Item& b) {
+      issue(iti, ci, b);
+      int i2 = iti, c2n = ci;
+      advance(i2, c2n);
+      if (i2 < NIT) {
+        iti = i2;
+        ci = c2n;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto one = [&](const Item& cur, Item& refill) -> bool {
+      issue_next(refill);
+      const int row = it * RPS + rg;
+      if (c == 0) begin_row(row);
+      fold(it, c, cur);
+      if (c == nch - 1) {
+        end_row(row);
+        // allocated slots beyond the last chunk (depth_alloc > depth_count rounded up to a chunk)
+        const int t = qw0 + row;
+        if (t < T) {
+          const u32x4 z = {0u, 0u, 0u, 0u};
+          for (int i = nch * kChunk; i < La; ++i) {
+            *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+            *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          }
+        }
+      }
+      advance(it, c);
+      return it < NIT;
+    };
+    Item bufA, bufB, bufC;
+    issue_next(bufA);
+    issue_next(bufB);
+    while (true) {
+      if (!one(bufA, bufC)) break;
+      if (!one(bufB, bufA)) break;
+      if (!one(bufC, bufB)) break;
+    }
+  };
+  constexpr std::integral_constant<int, 0> kDepthLast{};
+  constexpr std::integral_constant<int, 1> kDepthFirst{};
+
+  // Every other workgroup takes its depth slots before the key loop, so that the compute
+  // units do not all stream from / to HBM at the same time and all compute at the same time
+  // (same reasoning as in the forward kernel; ids are dealt round-robin to the 8 dies).
+  const bool depth_first = L > 0 && ((blockIdx.x >> 3) & 1) != 0;
+
   f32x16 dq[Tl::kDBlocks];
+  if (depth_first) {
+    depth_grad(kDepthFirst);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-  for (int db = 0; db < Tl::kDBlocks; ++db)
+    for (int db = 0; db < Tl::kDBlocks; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+      for (int bq = 0; bq < 4; ++bq) {
+        const f32x4 v = *(const f32x4*)(xw + l32 * C::kXRow + (db * 32 + bq * 8 + hi * 4) * 4);
+        dq[db][4 * bq] = v[0]; dq[db][4 * bq + 1] = v[1]; dq[db][4 * bq + 2] = v[2]; dq[db][4 * bq + 3] = v[3];
+      }
+    __syncthreads();  // every wave has its state: the buffer becomes the K/V ring
+  } else {
+#pragma unroll
+    for (int db = 0; db < Tl::kDBlocks; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+  }
 
   const int n_keys = p.causal ? min(T, q0 + 128) : T;
   const int nt = (n_keys + 63) / 64;
   const int wave_last = p.causal ? min(nt - 1, (qw0 + 31) / 64) : nt - 1;
   const int lim = p.causal ? min(qi, T - 1) : T - 1;  // last visible key of this lane's query
-  const float c2 = p.scale_log2;
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   TileLoader<D> ld;
   ld.init(wave, lane);
@@ -326,8 +531,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   }
   __syncthreads();
 
-  // ---- epilogue: accumulator layout -> row-major; depth slots; stores
-  unsigned char* xw = smem + wave * C::kXWave;
+  // ---- epilogue: accumulator layout -> row-major; depth slots (unless taken first); stores
 #pragma unroll
   for (int db = 0; db < Tl::kDBlocks; ++db)
 #pragma unroll
@@ -338,92 +542,21 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-  constexpr int LPR = Tl::kChunks, RPS = 64 / LPR;
-  const int rg = lane / LPR, l16 = lane % LPR;
-  const int L = p.depth_count, La = p.depth_alloc;
-  const size_t drow = (size_t)La * Tl::kRowBytes;
-  const char* Kdb = (const char*)p.Kdepth + (size_t)bh * T * drow;
-  const char* Vdb = (const char*)p.Vdepth + (size_t)bh * T * drow;
-  char* dKdb = (char*)p.dKdepth + (size_t)bh * T * drow;
-  char* dVdb = (char*)p.dVdepth + (size_t)bh * T * drow;
-  char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
-  constexpr int CH = 8;  // depth slots whose loads are in flight together
-
-  for (int it = 0; it < 32 / RPS; ++it) {
-    const int row = it * RPS + rg;
-    const int t = qw0 + row;
-    const int tc = min(t, T - 1);
-    const bool live = t < T;
-    const f32x4 a0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
-    const f32x4 a1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
-    float acc[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-    if (La > 0) {
-      const u32x4 qv = *(const u32x4*)(Qb + (size_t)tc * Tl::kRowBytes + l16 * 16);
-      const u32x4 gv = *(const u32x4*)(dOb + (size_t)tc * Tl::kRowBytes + l16 * 16);
-      const float l2 = LSEb[tc] * kLog2e;
-      const float dl = Db[tc];
-      float qx[8], gx[8];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        qx[2 * k] = bf16_lo(qv[k]);
-        qx[2 * k + 1] = bf16_hi(qv[k]);
-        gx[2 * k] = bf16_lo(gv[k]);
-        gx[2 * k + 1] = bf16_hi(gv[k]);
+  if (!depth_first) {
+    depth_grad(kDepthLast);
+  } else {
+    const int rg = lane / LPR, l16 = lane % LPR;
+    char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPS + rg, t = qw0 + row;
+      const f32x4 a0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
+      const f32x4 a1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
+      if (t < T) {
+        const float f = p.scale;
+        u32x4 ov = {pack_bf16(a0[0] * f, a0[1] * f), pack_bf16(a0[2] * f, a0[3] * f),
+                    pack_bf16(a1[0] * f, a1[1] * f), pack_bf16(a1[2] * f, a1[3] * f)};
+        *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
       }
-      const char* kd = Kdb + (size_t)tc * drow + l16 * 16;
-      const char* vd = Vdb + (size_t)tc * drow + l16 * 16;
-      char* dkd = dKdb + (size_t)tc * drow + l16 * 16;
-      char* dvd = dVdb + (size_t)tc * drow + l16 * 16;
-      for (int i0 = 0; i0 < L; i0 += CH) {
-        u32x4 kv[CH], vv[CH];
-#pragma unroll
-        for (int i = 0; i < CH; ++i) kv[i] = *(const u32x4*)(kd + (size_t)min(i0 + i, L - 1) * Tl::kRowBytes);
-#pragma unroll
-        for (int i = 0; i < CH; ++i) vv[i] = *(const u32x4*)(vd + (size_t)min(i0 + i, L - 1) * Tl::kRowBytes);
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-          float sdot = 0.f, gdot = 0.f;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            sdot = dot2_bf16(qv[k], kv[i][k], sdot);
-            gdot = dot2_bf16(gv[k], vv[i][k], gdot);
-          }
-          sdot = group_sum<LPR>(sdot);
-          gdot = group_sum<LPR>(gdot);
-          if (i0 + i < L) {  // uniform: slots past depth_count only re-read the last slot
-            const float pe = fast_exp2(sdot * c2 - l2);
-            const float e = pe * (gdot - dl);
-            const float es = e * p.scale;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              acc[2 * k] += e * bf16_lo(kv[i][k]);
-              acc[2 * k + 1] += e * bf16_hi(kv[i][k]);
-            }
-            if (live) {
-              u32x4 o1 = {pack_bf16(pe * gx[0], pe * gx[1]), pack_bf16(pe * gx[2], pe * gx[3]),
-                          pack_bf16(pe * gx[4], pe * gx[5]), pack_bf16(pe * gx[6], pe * gx[7])};
-              u32x4 o2 = {pack_bf16(es * qx[0], es * qx[1]), pack_bf16(es * qx[2], es * qx[3]),
-                          pack_bf16(es * qx[4], es * qx[5]), pack_bf16(es * qx[6], es * qx[7])};
-              *(u32x4*)(dvd + (size_t)(i0 + i) * Tl::kRowBytes) = o1;
-              *(u32x4*)(dkd + (size_t)(i0 + i) * Tl::kRowBytes) = o2;
-            }
-          }
-        }
-      }
-      if (live) {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
-          *(u32x4*)(dvd + (size_t)i * Tl::kRowBytes) = z;
-          *(u32x4*)(dkd + (size_t)i * Tl::kRowBytes) = z;
-        }
-      }
-    }
-    if (live) {
-      const float f = p.scale;
-      u32x4 ov = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f),
-                  pack_bf16(acc[4] * f, acc[5] * f), pack_bf16(acc[6] * f, acc[7] * f)};
-      *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
     }
   }
 }
