@@ -98,6 +98,7 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
  *        gradient slots >= depth_count are written as zero
  *   workspace: device scratch of at least moda_attn_bwd_workspace_bytes(s)
  *        bytes, 16-byte aligned; contents on entry are ignored.
+ * This build: bf16 only, Hq / Hk <= 8 (else MODA_ERR_UNSUPPORTED).
  */
 size_t moda_attn_bwd_workspace_bytes(const moda_shape* s);
 moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
@@ -105,6 +106,23 @@ moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, con
                           void* dQ, void* dKseq, void* dVseq, void* dKdepth, void* dVdepth,
                           void* workspace, size_t workspace_bytes, const moda_shape* s,
                           void* hip_stream);
+
+/*
+ * The "write" step of the depth stream (paper section 2.2: once a layer has run
+ * the operator, its key-value pair is appended to the depth stream so that the
+ * following layers can read it; an FFN layer appends the output of its own
+ * key-value projection the same way).  Copies the layer's K and V,
+ * [B, Hk, T, d], into slot `slot` of Kdepth and Vdepth, [B, Hk, T, depth_alloc, d];
+ * no other slot is touched.  A stack of layers allocates the cache once with
+ * depth_alloc = number of writers and lets layer l attend depth_count = l slots.
+ *   in : K, V                    device, read-only
+ *   out: Kdepth, Vdepth          device, slot `slot` of every position overwritten
+ * Uses B, Hk, T, d, depth_alloc and dtype of `s` (Hq, depth_count, causal and
+ * scale are validated as for the other calls but not used); 0 <= slot <
+ * depth_alloc, else MODA_ERR_SHAPE.  K / V must not overlap Kdepth / Vdepth.
+ */
+moda_status moda_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, int32_t slot,
+                              const moda_shape* s, void* hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* moda_status_string(moda_status st);

@@ -147,3 +147,16 @@ def bwd_rows(Q_rows, Kseq, Vseq, Kdepth_rows, Vdepth_rows, dO_rows, rows, depth_
     if rc != 0:
         raise ValueError("moda_ref_bwd_rows_f64 rejected its arguments")
     return dQ, dKd, dVd
+
+
+def depth_append(Kdepth, Vdepth, K, V, slot):
+    """The depth stream's write step (paper section 2.2: after the operator, the layer's
+    key-value pair is appended to the depth stream): returns copies of Kdepth, Vdepth
+    [B,Hk,T,depth_alloc,d] in which slot `slot` of every position holds K, V [B,Hk,T,d] and
+    every other slot is unchanged.  Plain array indexing, any dtype, no arithmetic."""
+    Kd, Vd = np.array(Kdepth, copy=True), np.array(Vdepth, copy=True)
+    if not 0 <= slot < Kd.shape[3]:
+        raise IndexError("slot out of range")
+    Kd[:, :, :, slot, :] = K
+    Vd[:, :, :, slot, :] = V
+    return Kd, Vd

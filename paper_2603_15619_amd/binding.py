@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MODA_LIB_PATH") or os.path.join(HERE, "libmoda.so")
 
 MODA_F32, MODA_BF16 = 0, 1
-EXPORTS = ("moda_attn_fwd", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd",
+EXPORTS = ("moda_attn_fwd", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd", "moda_depth_append",
            "moda_status_string", "moda_version", "moda_kernels_per_call")
 
 
@@ -50,6 +50,8 @@ def lib():
         L.moda_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.moda_attn_bwd.argtypes = [vp] * 14 + [ctypes.c_size_t, sp, vp]
         L.moda_attn_bwd.restype = ctypes.c_int
+        L.moda_depth_append.argtypes = [vp, vp, vp, vp, ctypes.c_int32, sp, vp]
+        L.moda_depth_append.restype = ctypes.c_int
         L.moda_status_string.argtypes = [ctypes.c_int]
         L.moda_status_string.restype = ctypes.c_char_p
         L.moda_version.restype = ctypes.c_int
@@ -165,3 +167,22 @@ def moda_attn_bwd(Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, dO, depth_count=None, c
                                    _ptr(dKd), _ptr(dVd), _ptr(workspace), ws_bytes,
                                    ctypes.byref(s), _stream(dev)))
     return dQ, dK, dV, dKd, dVd
+
+
+def moda_depth_append(K, V, Kdepth, Vdepth, slot):
+    """Depth-stream write step, in place on the current stream: K, V [B,Hk,T,d] become slot
+    `slot` of Kdepth, Vdepth [B,Hk,T,depth_alloc,d]."""
+    B, Hk, T, d = K.shape
+    dev, dt = K.device, K.dtype
+    _require(K, "K", (B, Hk, T, d), dt, dev)
+    _require(V, "V", (B, Hk, T, d), dt, dev)
+    if Kdepth is None or Vdepth is None or Kdepth.dim() != 5:
+        raise ValueError("Kdepth / Vdepth: expected [B,Hk,T,depth_alloc,d] tensors")
+    La = Kdepth.shape[3]
+    _require(Kdepth, "Kdepth", (B, Hk, T, La, d), dt, dev)
+    _require(Vdepth, "Vdepth", (B, Hk, T, La, d), dt, dev)
+    s = MODAShape(B, Hk, Hk, T, d, La, 0, 1, 0.0, _dtype_code(K))
+    with torch.cuda.device(dev):
+        _check(lib().moda_depth_append(_ptr(K), _ptr(V), _ptr(Kdepth), _ptr(Vdepth), int(slot),
+                                       ctypes.byref(s), _stream(dev)))
+    return Kdepth, Vdepth

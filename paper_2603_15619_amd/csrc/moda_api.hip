@@ -66,7 +66,8 @@ int moda_version(void) { return 100; }
 int moda_kernels_per_call(const moda_shape* s, int which) {
   if (check_shape(s) != MODA_OK || s->B == 0 || s->T == 0) return 0;
   if (which == 0) return 1;
-  return (s->dtype == MODA_BF16 && s->Hq == s->Hk) ? 3 : 0;
+  if (s->dtype != MODA_BF16 || s->Hq / s->Hk > moda::bwd_bf16_max_group()) return 0;
+  return (s->Hq != s->Hk && s->depth_alloc > 0) ? 4 : 3;
 }
 
 moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
@@ -99,6 +100,20 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
   return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
 }
 
+moda_status moda_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, int32_t slot,
+                              const moda_shape* s, void* hip_stream) {
+  moda_status st = check_shape(s);
+  if (st != MODA_OK) return st;
+  if (slot < 0 || slot >= s->depth_alloc) return MODA_ERR_SHAPE;
+  if (s->B == 0 || s->T == 0) return MODA_OK;
+  if (!K || !V || !Kdepth || !Vdepth) return MODA_ERR_NULL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Kdepth) || !aligned16(Vdepth)) return MODA_ERR_ALIGN;
+  const int esz = s->dtype == MODA_BF16 ? 2 : 4;
+  hipError_t e = moda::launch_depth_append(K, V, Kdepth, Vdepth, (long long)s->B * s->Hk * s->T, s->d * esz,
+                                           s->depth_alloc, slot, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
+}
+
 size_t moda_attn_bwd_workspace_bytes(const moda_shape* s) {
   if (check_shape(s) != MODA_OK) return 0;
   moda::BwdParams p{};
@@ -113,8 +128,8 @@ moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, con
                           void* hip_stream) {
   moda_status st = check_shape(s);
   if (st != MODA_OK) return st;
-  // this build's backward: bf16, one query head per key/value head
-  if (s->dtype != MODA_BF16 || s->Hq != s->Hk) return MODA_ERR_UNSUPPORTED;
+  // this build's backward: bf16, at most bwd_bf16_max_group() query heads per key/value head
+  if (s->dtype != MODA_BF16 || s->Hq / s->Hk > moda::bwd_bf16_max_group()) return MODA_ERR_UNSUPPORTED;
   if (s->B == 0 || s->T == 0) return MODA_OK;
   if (!Q || !Kseq || !Vseq || !O || !LSE || !dO || !dQ || !dKseq || !dVseq) return MODA_ERR_NULL;
   if (s->depth_count > 0 && (!Kdepth || !Vdepth)) return MODA_ERR_NULL;

@@ -17,7 +17,10 @@
 //            dQ^T += K^T dS^T; then, in a row-major epilogue, the depth slots of the
 //            query's own position give dKdepth, dVdepth (row-local, written once)
 //            and their share of dQ.
-// Grouped-query attention (Hq != Hk) is not handled here.
+// Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 8): the
+// gradients of the shared keys and values sum over the group.  dkdv walks the query
+// tiles of all G heads; the depth-slot gradients move from the dq kernel's epilogue to a
+// kernel of their own (depth_gqa) that holds the G heads of a position side by side.
 #include <type_traits>
 
 #include "moda_launch.h"
@@ -74,18 +77,16 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int T = p.T;
-  const int BH = p.B * p.Hq;
-  const int bh = blockIdx.x % BH;
-  const int jt = blockIdx.x / BH;  // key tiles in natural order: the first ones see the most queries
+  const int BHk = p.B * p.Hk;
+  const int bg = blockIdx.x % BHk;  // (batch, key/value head)
+  const int jt = blockIdx.x / BHk;  // key tiles in natural order: the first ones see the most queries
   const int j0 = jt * 128;
   const int kw0 = j0 + wave * 32;
+  const int G = p.Hq / p.Hk;        // query heads per key/value head: their gradients add up here
+  const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;  // first query head of the group
 
-  const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
-  const char* Kb = (const char*)p.Kseq + (size_t)bh * T * Tl::kRowBytes;
-  const char* Vb = (const char*)p.Vseq + (size_t)bh * T * Tl::kRowBytes;
-  const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
-  const float* LSEb = p.LSE + (size_t)bh * T;
-  const float* Db = p.delta + (size_t)bh * T;
+  const char* Kb = (const char*)p.Kseq + (size_t)bg * T * Tl::kRowBytes;
+  const char* Vb = (const char*)p.Vseq + (size_t)bg * T * Tl::kRowBytes;
 
   // resident K and V fragments of this wave's 32 keys (MFMA B operands: N = key, K = channels)
   bf16x8 kf[Tl::kDSteps], vf[Tl::kDSteps];
@@ -105,27 +106,33 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 
   const int nq = (T + 63) / 64;
   const int qt0 = p.causal ? j0 / 64 : 0;
+  const int span = nq - qt0;   // query tiles that see this key tile, per query head
+  const int n_items = G * span;  // work items: (query head of the group, query tile)
   const float c2 = p.scale_log2;
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   TileLoader<D> ld;
   ld.init(wave, lane);
 
-  auto issue = [&](int qt, int stage) {
+  auto issue = [&](int item, int stage) {
+    const int bh = bh0 + item / span, qt = qt0 + item % span;
+    const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
+    const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
     ld.issue(Qb, qt * 64, T, smem_addr + stage * C::kStageBytes);
     ld.issue(dOb, qt * 64, T, smem_addr + stage * C::kStageBytes + Tl::kBytes);
     if (tid < 64) {
       const int r = min(qt * 64 + tid, T - 1);
-      aux[stage * 128 + tid] = LSEb[r] * kLog2e;
-      aux[stage * 128 + 64 + tid] = Db[r];
+      aux[stage * 128 + tid] = p.LSE[(size_t)bh * T + r] * kLog2e;
+      aux[stage * 128 + 64 + tid] = p.delta[(size_t)bh * T + r];
     }
   };
 
-  issue(qt0, 0);
-  for (int qt = qt0; qt < nq; ++qt) {
-    const int stage = (qt - qt0) & 1;
+  if (n_items > 0) issue(0, 0);
+  for (int item = 0; item < n_items; ++item) {
+    const int stage = item & 1;
+    const int qt = qt0 + item % span;
     wait_copies();
     __syncthreads();
-    if (qt + 1 < nq) issue(qt + 1, stage ^ 1);
+    if (item + 1 < n_items) issue(item + 1, stage ^ 1);
 
     const int q0 = qt * 64;
     if (p.causal && q0 + 63 < kw0) continue;  // every query of the tile precedes this wave's keys
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    char* outb = (char*)(which ? p.dVseq : p.dKseq) + (size_t)bh * T * Tl::kRowBytes;
+    char* outb = (char*)(which ? p.dVseq : p.dKseq) + (size_t)bg * T * Tl::kRowBytes;
     const float f = which ? 1.0f : p.scale;
     for (int it = 0; it < 32 / RPS; ++it) {
       const int row = it * RPS + rg;
@@ -237,10 +244,12 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int qt = n_qt - 1 - blockIdx.x / BH;  // heavy (late) query tiles first
   const int q0 = qt * 128;
   const int qw0 = q0 + wave * 32;
+  const int G = p.Hq / p.Hk;
+  const int bg = (bh / p.Hq) * p.Hk + (bh % p.Hq) / G;  // (batch, key/value head) of this query head
 
   const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
-  const char* Kb = (const char*)p.Kseq + (size_t)bh * T * Tl::kRowBytes;
-  const char* Vb = (const char*)p.Vseq + (size_t)bh * T * Tl::kRowBytes;
+  const char* Kb = (const char*)p.Kseq + (size_t)bg * T * Tl::kRowBytes;
+  const char* Vb = (const char*)p.Vseq + (size_t)bg * T * Tl::kRowBytes;
   const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
   const float* LSEb = p.LSE + (size_t)bh * T;
   const float* Db = p.delta + (size_t)bh * T;
@@ -275,10 +284,11 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
     const int rg = lane / LPR, l16 = lane % LPR;
     const size_t drow = (size_t)La * Tl::kRowBytes;
     const size_t slab = (size_t)T * drow;
-    const char* Kdb = (const char*)p.Kdepth + (size_t)bh * slab;
-    const char* Vdb = (const char*)p.Vdepth + (size_t)bh * slab;
-    char* dKdb = (char*)p.dKdepth + (size_t)bh * slab;
-    char* dVdb = (char*)p.dVdepth + (size_t)bh * slab;
+    // (this phase only runs when every key/value head serves one query head: bg == bh)
+    const char* Kdb = (const char*)p.Kdepth + (size_t)bg * slab;
+    const char* Vdb = (const char*)p.Vdepth + (size_t)bg * slab;
+    char* dKdb = (char*)p.dKdepth + (size_t)bg * slab;
+    char* dVdb = (char*)p.dVdepth + (size_t)bg * slab;
     char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
     // bounds-checked raw buffers: slots of a chunk past the end of the slab read as zero
     // (slots past depth_count or depth_alloc are masked below)
@@ -447,10 +457,24 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   // Every other workgroup takes its depth slots before the key loop, so that the compute
   // units do not all stream from / to HBM at the same time and all compute at the same time
   // (same reasoning as in the forward kernel; ids are dealt round-robin to the 8 dies).
-  const bool depth_first = L > 0 && ((blockIdx.x >> 3) & 1) != 0;
+  // With grouped queries (G > 1) the depth-slot gradients sum over the group's query heads:
+  // moda_bwd_depth_gqa_kernel has computed them before this kernel and has left the depth
+  // share of dQ (not yet multiplied by the softmax scale, rounded to bf16) in the dQ buffer.
+  const bool external = G > 1;
+  const bool depth_first = !external && L > 0 && ((blockIdx.x >> 3) & 1) != 0;
 
   f32x16 dq[Tl::kDBlocks];
-  if (depth_first) {
+  if (external && La > 0) {
+    const char* src = (const char*)p.dQ + ((size_t)bh * T + qrow) * Tl::kRowBytes;
+#pragma unroll
+    for (int db = 0; db < Tl::kDBlocks; ++db)
+#pragma unroll
+      for (int bq = 0; bq < 4; ++bq) {
+        const u32x2 v = *(const u32x2*)(src + (db * 32 + bq * 8 + hi * 4) * 2);
+        dq[db][4 * bq] = bf16_lo(v[0]); dq[db][4 * bq + 1] = bf16_hi(v[0]);
+        dq[db][4 * bq + 2] = bf16_lo(v[1]); dq[db][4 * bq + 3] = bf16_hi(v[1]);
+      }
+  } else if (depth_first) {
     depth_grad(kDepthFirst);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -542,7 +566,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  if (!depth_first) {
+  if (!depth_first && !external) {
     depth_grad(kDepthLast);
   } else {
     const int rg = lane / LPR, l16 = lane % LPR;
@@ -561,28 +585,144 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   }
 }
 
+// ---------------------------------------------------------------- depth-slot gradients, grouped queries
+// One row = one (batch, key/value head, position); d/8 lanes x 8 channels per row.  The GT
+// (>= G) query heads of the group are resident (their Q and dO rows, LSE, delta, and their
+// depth share of dQ); the row's slots stream by, one prefetched ahead.  Per slot i:
+//   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (one rounding each),
+//   dQ_h     += e_{h,i} k_i          (left in the dQ buffer, unscaled, for the dQ kernel).
+template <int D, int GT>
+__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
+  constexpr int LPR = D / 8, ROWS = 256 / LPR, RB = D * 2;
+  const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
+  const int tid = threadIdx.x, l16 = tid % LPR;
+  const long long row = (long long)blockIdx.x * ROWS + tid / LPR;  // (b * Hk + g) * T + t
+  const long long n_rows = (long long)p.B * p.Hk * T;
+  const bool live = row < n_rows;
+  const long long rc = live ? row : n_rows - 1;
+  const int t = (int)(rc % T);
+  const int bg = (int)(rc / T);
+  const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;
+  const float c2 = p.scale_log2;
+
+  u32x4 q[GT], g[GT];
+  float l2[GT], dl[GT], dq[GT][8];
+#pragma unroll
+  for (int j = 0; j < GT; ++j) {
+    const int bh = bh0 + min(j, G - 1);  // heads past the group repeat the last one with weight zero
+    q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
+    g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
+    l2[j] = p.LSE[(size_t)bh * T + t] * kLog2e;
+    dl[j] = p.delta[(size_t)bh * T + t];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dq[j][k] = 0.f;
+  }
+  const size_t drow = (size_t)La * RB;
+  const char* kd = (const char*)p.Kdepth + (size_t)rc * drow + l16 * 16;
+  const char* vd = (const char*)p.Vdepth + (size_t)rc * drow + l16 * 16;
+  char* dkd = (char*)p.dKdepth + (size_t)rc * drow + l16 * 16;
+  char* dvd = (char*)p.dVdepth + (size_t)rc * drow + l16 * 16;
+
+  u32x4 kn = {0u, 0u, 0u, 0u}, vn = kn;
+  if (L > 0) {
+    kn = __builtin_nontemporal_load((const u32x4*)kd);
+    vn = __builtin_nontemporal_load((const u32x4*)vd);
+  }
+  for (int i = 0; i < L; ++i) {
+    const u32x4 kv = kn, vv = vn;
+    const int inext = min(i + 1, L - 1);
+    kn = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
+    vn = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
+    float kx[8], ak[8], av[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      kx[2 * k] = bf16_lo(kv[k]);
+      kx[2 * k + 1] = bf16_hi(kv[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ak[k] = av[k] = 0.f;
+#pragma unroll
+    for (int j = 0; j < GT; ++j) {
+      float sdot = 0.f, gdot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        sdot = dot2_bf16(q[j][k], kv[k], sdot);
+        gdot = dot2_bf16(g[j][k], vv[k], gdot);
+      }
+      sdot = group_sum<LPR>(sdot);
+      gdot = group_sum<LPR>(gdot);
+      const float pe = j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
+      const float e = pe * (gdot - dl[j]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        av[2 * k] += pe * bf16_lo(g[j][k]);
+        av[2 * k + 1] += pe * bf16_hi(g[j][k]);
+        ak[2 * k] += e * bf16_lo(q[j][k]);
+        ak[2 * k + 1] += e * bf16_hi(q[j][k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dq[j][k] += e * kx[k];
+    }
+    if (live) {
+      const float f = p.scale;
+      const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
+      const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
+                        pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
+      __builtin_nontemporal_store(o1, (u32x4*)(dvd + (size_t)i * RB));
+      __builtin_nontemporal_store(o2, (u32x4*)(dkd + (size_t)i * RB));
+    }
+  }
+  if (live) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
+      *(u32x4*)(dvd + (size_t)i * RB) = z;
+      *(u32x4*)(dkd + (size_t)i * RB) = z;
+    }
+#pragma unroll
+    for (int j = 0; j < GT; ++j)
+      if (j < G) {
+        const u32x4 ov = {pack_bf16(dq[j][0], dq[j][1]), pack_bf16(dq[j][2], dq[j][3]),
+                          pack_bf16(dq[j][4], dq[j][5]), pack_bf16(dq[j][6], dq[j][7])};
+        *(u32x4*)((char*)p.dQ + ((size_t)(bh0 + j) * T + t) * RB + l16 * 16) = ov;
+      }
+  }
+}
+
 // ---------------------------------------------------------------- launchers
 size_t bwd_bf16_workspace_bytes(const BwdParams& p) { return (size_t)p.B * p.Hq * p.T * sizeof(float); }
 
-hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream) {
+int bwd_bf16_max_group() { return 8; }
+
+template <int D>
+static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
   const long long rows = (long long)p.B * p.Hq * p.T;
-  const int BH = p.B * p.Hq;
-  const long long g_delta = (rows * (d / 8) + 255) / 256;
-  const long long g_dkdv = (long long)BH * ((p.T + 127) / 128);
-  const long long g_dq = g_dkdv;
-  if (g_delta > 0x7fffffffLL || g_dkdv > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (d == 128) {
-    hipLaunchKernelGGL(moda_bwd_delta_kernel<128>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.delta, rows);
-    hipLaunchKernelGGL(moda_bwd_dkdv_kernel<128>, dim3((unsigned)g_dkdv), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(moda_bwd_dq_kernel<128>, dim3((unsigned)g_dq), dim3(256), 0, stream, p);
-  } else if (d == 64) {
-    hipLaunchKernelGGL(moda_bwd_delta_kernel<64>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.delta, rows);
-    hipLaunchKernelGGL(moda_bwd_dkdv_kernel<64>, dim3((unsigned)g_dkdv), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(moda_bwd_dq_kernel<64>, dim3((unsigned)g_dq), dim3(256), 0, stream, p);
-  } else {
-    return hipErrorInvalidValue;
+  const int G = p.Hq / p.Hk;
+  const long long g_delta = (rows * (D / 8) + 255) / 256;
+  const long long n_kt = (p.T + 127) / 128;
+  const long long g_dkdv = (long long)p.B * p.Hk * n_kt;
+  const long long g_dq = (long long)p.B * p.Hq * n_kt;
+  const long long kv_rows = (long long)p.B * p.Hk * p.T;
+  const long long g_depth = (kv_rows * (D / 8) + 255) / 256;
+  if (g_delta > 0x7fffffffLL || g_dq > 0x7fffffffLL || g_depth > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (G > bwd_bf16_max_group()) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.delta, rows);
+  if (G > 1 && p.depth_alloc > 0) {
+    if (G <= 2)
+      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 2>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
+    else if (G <= 4)
+      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 4>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 8>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
   }
+  hipLaunchKernelGGL(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL(moda_bwd_dq_kernel<D>, dim3((unsigned)g_dq), dim3(256), 0, stream, p);
   return hipGetLastError();
+}
+
+hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream) {
+  if (d == 128) return launch_bwd_bf16_d<128>(p, stream);
+  if (d == 64) return launch_bwd_bf16_d<64>(p, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace moda

@@ -10,8 +10,15 @@ int fwd_bf16_tile_rows(int waves);
 hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t stream);
 hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream);
 
-// Backward (bf16, Hq == Hk): delta, dK/dV and dQ/depth kernels on `stream`.
+// Backward (bf16, Hq / Hk <= bwd_bf16_max_group()): delta, [depth slots of grouped queries,]
+// dK/dV and dQ(/depth) kernels on `stream`.
+int bwd_bf16_max_group();
 size_t bwd_bf16_workspace_bytes(const BwdParams& p);
 hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream);
+
+// Depth-stream write step: rows of K / V [rows, row_bytes] into slot `slot` of
+// [rows, depth_alloc, row_bytes].
+hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, long long rows,
+                               int row_bytes, int depth_alloc, int slot, hipStream_t stream);
 
 }  // namespace moda

@@ -41,10 +41,11 @@ def compare(name, got, ref):
     assert worst <= ATOL, name
 
 
-def check_full(B, H, T, d, L, seed, causal=True, depth_alloc=None, scale=None):
-    print("bwd case", dict(B=B, H=H, T=T, d=d, L=L, seed=seed, causal=causal, depth_alloc=depth_alloc),
+def check_full(B, H, T, d, L, seed, causal=True, depth_alloc=None, scale=None, Hk=None):
+    Hk = H if Hk is None else Hk
+    print("bwd case", dict(B=B, Hq=H, Hk=Hk, T=T, d=d, L=L, seed=seed, causal=causal, depth_alloc=depth_alloc),
           flush=True)
-    inp = synth.make_inputs(B, H, H, T, d, L, dtype="bf16", seed=seed, device="cuda",
+    inp = synth.make_inputs(B, H, Hk, T, d, L, dtype="bf16", seed=seed, device="cuda",
                             depth_alloc=depth_alloc, with_dO=True)
     grads = run_gpu(inp, L, causal, scale)
     ref = R.bwd(*(synth.to_f64(inp[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth", "dO")),
@@ -79,9 +80,27 @@ def test_bwd_deterministic():
 def test_bwd_rejects_unsupported():
     from paper_2603_15619_amd import MODAError
 
-    inp = synth.make_inputs(1, 4, 2, 64, 128, 2, dtype="bf16", seed=25, device="cuda", with_dO=True)
-    with pytest.raises(MODAError):  # grouped-query backward is not built
+    inp = synth.make_inputs(1, 16, 1, 64, 128, 2, dtype="bf16", seed=25, device="cuda", with_dO=True)
+    with pytest.raises(MODAError):  # more than 8 query heads per key/value head
         run_gpu(inp, 2)
+
+
+@pytest.mark.parametrize("Hq,Hk,T,d,L,La", [(4, 2, 300, 128, 5, None), (8, 1, 200, 64, 3, 4), (6, 2, 257, 128, 0, 2),
+                                            (8, 2, 130, 64, 9, None), (2, 1, 64, 128, 0, 0), (16, 2, 500, 64, 17, None)])
+def test_bwd_grouped_queries(Hq, Hk, T, d, L, La):
+    """G = Hq / Hk query heads share a key/value head: the gradients of the shared sequence
+    and depth keys / values sum over the group (G = 2, 3, 4, 8; the paper's models use G = 2,
+    its kernel benchmarks G = 8)."""
+    check_full(2, Hq, T, d, L, 500 + T + L, depth_alloc=La, Hk=Hk)
+
+
+def test_bwd_grouped_queries_non_causal_deterministic():
+    check_full(1, 4, 333, 128, 3, 26, causal=False, Hk=2)
+    inp = synth.make_inputs(1, 8, 2, 400, 64, 7, dtype="bf16", seed=27, device="cuda", with_dO=True)
+    a = run_gpu(inp, 7)
+    b = run_gpu(inp, 7)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
 
 
 def test_config5_t256_slice_full():

@@ -344,3 +344,23 @@ def test_bad_arguments_are_rejected():
         R.fwd(Q, K, V, Kd, Vd, depth_count=7)  # more slots than allocated
     with pytest.raises(ValueError):
         R.fwd_rows(Q[:, :, :1], K, V, Kd[:, :, :1], Vd[:, :, :1], [99])
+
+
+def test_depth_append_builds_the_stacked_stream():
+    """Write step: appending the layers' K / V one slot at a time to an empty cache gives
+    the layers stacked along the slot axis (checked against numpy's own stacking routine),
+    and a write never touches another slot."""
+    rng = np.random.default_rng(5)
+    B, Hk, T, d, La = 2, 3, 7, 4, 5
+    Ks = [rng.standard_normal((B, Hk, T, d)) for _ in range(La)]
+    Vs = [rng.standard_normal((B, Hk, T, d)) for _ in range(La)]
+    Kd = np.full((B, Hk, T, La, d), np.nan)
+    Vd = np.full((B, Hk, T, La, d), np.nan)
+    for order, slot in enumerate([3, 0, 4, 1, 2]):
+        before_k = Kd.copy()
+        Kd, Vd = R.depth_append(Kd, Vd, Ks[slot], Vs[slot], slot)
+        others = [i for i in range(La) if i != slot]
+        assert np.array_equal(Kd[:, :, :, others], before_k[:, :, :, others], equal_nan=True)
+    assert np.array_equal(Kd, np.stack(Ks, axis=3)) and np.array_equal(Vd, np.stack(Vs, axis=3))
+    with pytest.raises(IndexError):
+        R.depth_append(Kd, Vd, Ks[0], Vs[0], La)
