@@ -383,9 +383,16 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
         sdot = group_sum<LPR>(sdot);
         gdot = group_sum<LPR>(gdot);
         const int slot = c * kChunk + i;
-        if (slot < La) {  // uniform
-          // slots past depth_count: weight zero, so zero gradients are written
-          const float pe = slot < L ? fast_exp2(sdot * c2 - b.l2) : 0.f;
+        if (slot >= L) {  // uniform
+          // slots past depth_count may hold anything (NaN included) and take no part; those
+          // that are allocated get zero gradients
+          if (slot < La && live) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            __builtin_amdgcn_raw_buffer_store_b128(z, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
+            __builtin_amdgcn_raw_buffer_store_b128(z, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
+          }
+        } else {
+          const float pe = fast_exp2(sdot * c2 - b.l2);
           const float e = pe * (gdot - b.dl);
           const float es = e * p.scale;
 #pragma unroll

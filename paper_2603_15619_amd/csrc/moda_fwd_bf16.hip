@@ -538,6 +538,9 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       for (int k = 0; k < 8; ++k) o[k] *= al;
 #pragma unroll
       for (int i = 0; i < kDepthChunk; ++i) {
+        // (uniform) slots past depth_count may hold anything, NaN included (a cache that is
+        // still being filled): their values must not even be multiplied by a zero weight
+        if (c * kDepthChunk + i >= L) break;
         const float pw = fast_exp2(sc[i] * c2 - mc);
         l += pw;
         // weight rounded to bf16 (as P is for the sequence keys) and placed in the low or

@@ -132,3 +132,22 @@ def test_config5_full_size_sampled():
         compare("dVseq[%d,%d]" % (b, h), dV[b:b + 1, h:h + 1], ref[2])
     for g in (dQ, dK, dV, dKd, dVd):
         assert torch.isfinite(g.float()).all()
+
+
+@pytest.mark.parametrize("Hq,Hk,L", [(2, 2, 1), (2, 2, 5), (2, 2, 7), (4, 2, 3)])
+def test_bwd_unattended_slots_may_hold_nan(Hq, Hk, L):
+    """Slots >= depth_count of a cache that is still being filled hold NaN bit patterns: they
+    take no part, and their gradients are written as zero."""
+    inp = synth.make_inputs(1, Hq, Hk, 200, 128, L, dtype="bf16", seed=28, device="cuda", depth_alloc=8,
+                            with_dO=True)
+    inp["Kdepth"][:, :, :, L:] = float("nan")
+    inp["Vdepth"][:, :, :, L:] = float("nan")
+    grads = run_gpu(inp, L)
+    clean = {k: (None if v is None else v.clone()) for k, v in inp.items()}
+    clean["Kdepth"][:, :, :, L:] = 0
+    clean["Vdepth"][:, :, :, L:] = 0
+    ref = R.bwd(*(synth.to_f64(clean[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth", "dO")), depth_count=L)
+    for name, g, r in zip(NAMES, grads, ref):
+        compare(name, g, r)
+    assert torch.count_nonzero(grads[3][:, :, :, L:].float()) == 0
+    assert torch.count_nonzero(grads[4][:, :, :, L:].float()) == 0

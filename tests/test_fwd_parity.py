@@ -157,3 +157,16 @@ def test_config3_long_context_sampled():
 @pytest.mark.parametrize("T,L", [(1024, 1), (1024, 31), (4096, 7), (16384, 15)])
 def test_config4_sweep_points_sampled(T, L):
     check_sampled(4, 16, 16, T, 128, L, "bf16", 3, n_random=16)
+
+
+@pytest.mark.parametrize("L", [1, 4, 5, 7])
+def test_unattended_slots_may_hold_nan(L):
+    """A cache that is still being filled: slots >= depth_count hold NaN bit patterns and
+    must take no part, not even multiplied by a zero weight."""
+    inp = synth.make_inputs(1, 2, 2, 300, 128, L, dtype="bf16", seed=14, device="cuda", depth_alloc=8)
+    inp["Kdepth"][:, :, :, L:] = float("nan")
+    inp["Vdepth"][:, :, :, L:] = float("nan")
+    O, LSE = run_gpu(inp, L)
+    Oref, Lref = R.fwd(*(synth.to_f64(inp[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth")), depth_count=L)
+    assert np.abs(synth.to_f64(O) - Oref).max() <= TOL["bf16"][0]
+    assert np.abs(synth.to_f64(LSE) - Lref).max() <= TOL["bf16"][1]
