@@ -32,6 +32,7 @@ WORKLOADS = {
     "bwd_layer_1p5b_4k": (8, 16, 16, 4096, 128, 15, "bf16"),   # BASELINE configs[4] (backward)
     "copy_calibration": None,  # plain device copy of known size, for scaling the HBM byte counters
     "sweep": None,             # BASELINE configs[3]: B=4 H=16 d=128, T x depth_count grid
+    "paper_table2": None,      # the paper's Table 2 shapes (d=64, grouped queries, 64..256 slots), fwd+bwd
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 vector
 
@@ -96,6 +97,55 @@ def run_sweep(args):
                            "depth_gbps_over_call": round(depth_bytes / (ms * 1e-3) / 1e9, 1)})
     print(json.dumps({"metric": "MoDA attn fwd sweep (B=4 H=16 d=128 bf16 causal)", "steps": args.steps,
                       "warmup": args.warmup, "points": points}))
+
+
+# Table 2 of the paper: (row, T, G, Hq, Hk, L, its FlashAttention-2 ms, its MoDA ms) -- forward and
+# backward together, one A100, bf16, B=1, d=64; quoted as context (other hardware, Triton kernels).
+PAPER_TABLE2 = [
+    (1, 4096, 8, 64, 8, 64, 7.970, 10.750), (2, 8192, 8, 64, 8, 64, 28.700, 35.427),
+    (3, 16384, 8, 64, 8, 64, 116.700, 127.661), (4, 32768, 8, 64, 8, 64, 459.854, 480.914),
+    (5, 65536, 8, 64, 8, 64, 1831.668, 1883.026), (6, 16384, 2, 16, 8, 64, 28.982, 39.741),
+    (7, 16384, 4, 32, 8, 64, 58.071, 68.939), (9, 16384, 16, 128, 8, 64, 233.700, 244.900),
+    (10, 16384, 32, 256, 8, 64, 467.107, 480.767), (12, 16384, 8, 64, 8, 128, 116.700, 138.224),
+    (13, 16384, 8, 64, 8, 256, 116.700, 167.958),
+]
+
+
+def run_paper_table2(args):
+    """Forward + backward time at the paper's Table 2 shapes (rows 8 and 11 repeat row 3), with and
+    without the depth slots, and the paper's "extra time" figure (MoDA - FA) / MoDA formed the same
+    way.  Rows whose group size exceeds what the backward supports are timed forward-only."""
+    from paper_2603_15619_amd import moda_attn_bwd, moda_attn_fwd, synth
+
+    rows = []
+    for (no, T, G, Hq, Hk, L, p_fa, p_moda) in PAPER_TABLE2:
+        if args.rows and no not in args.rows:
+            continue
+        inp = synth.make_inputs(1, Hq, Hk, T, 64, L, dtype="bf16", seed=5, device="cuda", with_dO=True)
+        O = torch.empty_like(inp["Q"])
+        LSE = torch.empty((1, Hq, T), dtype=torch.float32, device="cuda")
+        ws = torch.empty(4 * Hq * T + 256, dtype=torch.uint8, device="cuda")
+        with_bwd = G <= 8
+        out = {"row": no, "T": T, "G": G, "Hq": Hq, "Hk": Hk, "depth_count": L, "backward_included": with_bwd,
+               "paper_a100_ms": {"fa2": p_fa, "moda": p_moda, "extra_pct": round(100 * (p_moda - p_fa) / p_moda, 2)}}
+        for name, kd, vd, dc in (("fa", None, None, 0), ("moda", inp["Kdepth"], inp["Vdepth"], L)):
+            def step():
+                moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], kd, vd, depth_count=dc, out=O, lse=LSE)
+                if with_bwd:
+                    moda_attn_bwd(inp["Q"], inp["Kseq"], inp["Vseq"], kd, vd, O, LSE, inp["dO"], depth_count=dc,
+                                  workspace=ws)
+            steps = max(2, min(args.steps, int(2e4 / T) + 2))
+            ms, _, _ = time_calls(step, steps, 1)
+            out[name + "_ms"] = round(ms, 3)
+        out["extra_pct"] = round(100 * (out["moda_ms"] - out["fa_ms"]) / out["moda_ms"], 2)
+        out["fa_over_moda"] = round(out["fa_ms"] / out["moda_ms"], 4)
+        flops = (fwd_flops(1, Hq, T, 64, L) + (bwd_flops(1, Hq, T, 64, L) if with_bwd else 0.0))
+        out["moda_tflops"] = round(flops / (out["moda_ms"] * 1e-3) / 1e12, 1)
+        rows.append(out)
+        del inp, O, LSE, ws
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "MoDA vs own causal FA at the paper's Table 2 shapes (B=1 d=64 bf16, fwd+bwd)",
+                      "steps": args.steps, "rows": rows}))
 
 
 def run_backward(args, B, Hq, Hk, T, d, L, dtype):
@@ -179,6 +229,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fa", action="store_true", help="skip the depth_count=0 comparison run")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--rows", type=int, nargs="*", default=None, help="paper_table2: only these row numbers")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (every (b,h) is independent, "
@@ -194,6 +245,8 @@ def main():
         return run_copy_calibration(args)
     if args.workload == "sweep":
         return run_sweep(args)
+    if args.workload == "paper_table2":
+        return run_paper_table2(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
     if args.depth_count is not None:
         L = args.depth_count
@@ -238,7 +291,7 @@ def main():
                      "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_TFLOPS[dtype], 4),
                      "traffic": measured_traffic(args.workload, "fwd"),
-                     "kernel": "moda_fwd_%s_kernel<%d>" % (dtype, d),
+                     "kernel": ("moda_fwd_bf16_kernel<%d, 8>" % d) if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
                      "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
                      "flops_per_launch": flops},
     }

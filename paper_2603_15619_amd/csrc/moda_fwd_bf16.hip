@@ -397,7 +397,18 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   // so that, with ids dealt round-robin to the 8 XCDs, one XCD keeps serving
   // the same heads and its L2 sees each K/V tile from several workgroups.
   const int BH = p.B * p.Hq;
-  const int bh = blockIdx.x % BH;
+  int bh = blockIdx.x % BH;
+  {
+    // Grouped queries: the G heads of a group read the same sequence AND depth keys / values.
+    // Ids are dealt round-robin to the 8 dies, so with ids walking over the heads the group
+    // would be spread over all 8 L2 caches and everything fetched 8 times.  Instead, the ids
+    // that land on one die (equal id mod 8) walk over the heads of one group first.
+    const int G = p.Hq / p.Hk;
+    if (G > 1 && BH % (8 * G) == 0) {
+      const int die = bh & 7, m = bh >> 3;
+      bh = ((m / G) * 8 + die) * G + m % G;
+    }
+  }
   const int qt = p.n_qtiles - 1 - blockIdx.x / BH;
   const int b = bh / p.Hq;
   const int h = bh - b * p.Hq;

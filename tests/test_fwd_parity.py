@@ -170,3 +170,11 @@ def test_unattended_slots_may_hold_nan(L):
     Oref, Lref = R.fwd(*(synth.to_f64(inp[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth")), depth_count=L)
     assert np.abs(synth.to_f64(O) - Oref).max() <= TOL["bf16"][0]
     assert np.abs(synth.to_f64(LSE) - Lref).max() <= TOL["bf16"][1]
+
+
+@pytest.mark.parametrize("B,Hq,Hk,T,d,L", [(1, 16, 8, 300, 64, 3), (2, 32, 4, 260, 128, 5), (1, 64, 8, 130, 64, 9)])
+def test_grouped_queries_many_heads(B, Hq, Hk, T, d, L):
+    """Head counts at which the kernel re-maps workgroup ids so that the query heads of one
+    group land on the same die (B * Hq a multiple of 8 * group size); the paper's kernel
+    benchmark shape Hq = 64, Hk = 8, d = 64 among them."""
+    check_full(B, Hq, Hk, T, d, L, "bf16", 800 + Hq + T)
