@@ -290,8 +290,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
     char* dKdb = (char*)p.dKdepth + (size_t)bg * slab;
     char* dVdb = (char*)p.dVdepth + (size_t)bg * slab;
     char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
-    // bounds-checked raw buffers: slots of a chunk past the end of the slab read as zero
-    // (slots past depth_count or depth_alloc are masked below)
+    // raw buffers with 32-bit offsets
     const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Kdb, 0, (int)(unsigned)slab, 0x00020000);
     const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Vdb, 0, (int)(unsigned)slab, 0x00020000);
     const __amdgpu_buffer_rsrc_t dkd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dKdb, 0, (int)(unsigned)slab, 0x00020000);
@@ -351,13 +350,13 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
       b.l2 = LSEb[tc] * kLog2e;
       b.dl = Db[tc];
       const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
-      const int soff = c * kChunk * Tl::kRowBytes;
+      // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
 #pragma unroll
       for (int i = 0; i < kChunk; ++i)
-        b.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * Tl::kRowBytes, soff, 2);
+        b.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
 #pragma unroll
       for (int i = 0; i < kChunk; ++i)
-        b.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * Tl::kRowBytes, soff, 2);
+        b.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
     };
     auto fold = [&](int it, int c, const Item& b) {
       const int t = qw0 + it * RPS + rg;

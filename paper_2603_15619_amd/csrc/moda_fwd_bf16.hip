@@ -506,9 +506,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       u32x4 k[kDepthChunk], v[kDepthChunk];
     };
     const int nch = (L + kDepthChunk - 1) / kDepthChunk;
-    // The depth slabs are read through bounds-checked raw buffers with 32-bit offsets:
-    // a chunk's slots past depth_alloc at the very end of the slab read as zero, and no
-    // index clamping is needed (slots past depth_count get weight zero below).
+    // The depth slabs are read through raw buffers with 32-bit offsets.
     const size_t slab_bytes = (size_t)T * drow;
     const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
@@ -518,13 +516,16 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
       buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
       const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
-      const int soff = c * kDepthChunk * C::kRowBytes;
+      // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
+      // rather than fetching bytes that nothing uses
 #pragma unroll
       for (int i = 0; i < kDepthChunk; ++i)
-        buf.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+        buf.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff, min(c * kDepthChunk + i, L - 1) * C::kRowBytes,
+                                                         kStreamOnce);
 #pragma unroll
       for (int i = 0; i < kDepthChunk; ++i)
-        buf.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff + i * C::kRowBytes, soff, kStreamOnce);
+        buf.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff, min(c * kDepthChunk + i, L - 1) * C::kRowBytes,
+                                                         kStreamOnce);
     };
     auto fold = [&](int c, const DepthBuf& buf) {
       float sc[kDepthChunk];
