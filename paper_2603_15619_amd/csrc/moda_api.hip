@@ -90,8 +90,20 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
   p.causal = s->causal;
   p.scale = resolve_scale(s);
   p.scale_log2 = p.scale * 1.4426950408889634f;
+  // grouped queries: as many heads of a group per tile as divide both the group and the waves
+  const int G = s->Hq / s->Hk;
   const int waves = fwd_waves_per_workgroup(s);
-  const int rows = moda::fwd_bf16_tile_rows(waves);
+  p.heads_per_tile = 1;
+  for (int gt = waves; gt > 1; gt /= 2)
+    if (G % gt == 0) {
+      p.heads_per_tile = gt;
+      break;
+    }
+  if (const char* e = getenv("MODA_FWD_HEADS_PER_TILE")) {  // experiments
+    const int gt = atoi(e);
+    if (gt >= 1 && waves % gt == 0 && G % gt == 0) p.heads_per_tile = gt;
+  }
+  const int rows = moda::fwd_bf16_tile_rows(waves) / p.heads_per_tile;  // positions per tile
   p.n_qtiles = (s->T + rows - 1) / rows;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -31,7 +31,8 @@ struct FwdParams {
   int causal;
   float scale;       // softmax scale (natural units)
   float scale_log2;  // scale * log2(e): logits are exponentiated with exp2
-  int n_qtiles;      // query tiles per (b, h)
+  int n_qtiles;      // tiles along the sequence (bf16 kernel: see heads_per_tile)
+  int heads_per_tile;  // bf16 kernel: query heads of one group that share a tile (divides Hq/Hk and the waves)
 };
 
 // Kernel arguments of the backward pass (bf16, Hq == Hk).

@@ -393,33 +393,40 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-  // Heavy (late) query tiles first; consecutive workgroup ids walk over (b, h)
-  // so that, with ids dealt round-robin to the 8 XCDs, one XCD keeps serving
-  // the same heads and its L2 sees each K/V tile from several workgroups.
-  const int BH = p.B * p.Hq;
-  int bh = blockIdx.x % BH;
-  {
-    // Grouped queries: the G heads of a group read the same sequence AND depth keys / values.
-    // Ids are dealt round-robin to the 8 dies, so with ids walking over the heads the group
-    // would be spread over all 8 L2 caches and everything fetched 8 times.  Instead, the ids
-    // that land on one die (equal id mod 8) walk over the heads of one group first.
-    const int G = p.Hq / p.Hk;
-    if (G > 1 && BH % (8 * G) == 0) {
-      const int die = bh & 7, m = bh >> 3;
-      bh = ((m / G) * 8 + die) * G + m % G;
-    }
+  // ---- What this workgroup computes.  A tile is kBM (position, query head) pairs of one
+  // key/value head: kBM / GT consecutive positions x GT query heads of its group (GT divides
+  // both the group size and the number of waves; GT = 1 without grouped queries).  All rows of
+  // the tile read the same sequence K/V tiles and, position by position, the same depth slots
+  // (the paper flattens the G heads of a group into the row axis for the same reason).  Wave w
+  // owns head w % GT and the 32 positions of block w / GT in the key loop.
+  // Heavy (late) tiles first; consecutive workgroup ids walk over (batch, key/value head,
+  // head subset), so that, with ids dealt round-robin to the 8 dies, one die keeps serving the
+  // same heads and its L2 sees each K/V tile from several workgroups.
+  const int G = p.Hq / p.Hk;
+  const int GT = p.heads_per_tile;
+  const int sub = G / GT;                 // head subsets per group
+  const int NBH = p.B * p.Hk * sub;
+  int tbh = blockIdx.x % NBH;
+  if (sub > 1 && NBH % (8 * sub) == 0) {
+    // the head subsets of one group read the same K/V: the ids that land on one die (equal id
+    // mod 8) walk over the subsets of one group first, so that one L2 serves the group
+    const int die = tbh & 7, m = tbh >> 3;
+    tbh = ((m / sub) * 8 + die) * sub + m % sub;
   }
-  const int qt = p.n_qtiles - 1 - blockIdx.x / BH;
-  const int b = bh / p.Hq;
-  const int h = bh - b * p.Hq;
-  const int g = h / (p.Hq / p.Hk);
+  const int qt = p.n_qtiles - 1 - blockIdx.x / NBH;
+  const int bg = tbh / sub;               // (batch, key/value head)
+  const int b = bg / p.Hk;
+  const int g = bg - b * p.Hk;
+  const int hb = b * p.Hq + g * G + (tbh - bg * sub) * GT;  // first head of the tile, as an index into [B*Hq]
   const int T = p.T;
-  const int q0 = qt * kBM;
-  const int qw0 = q0 + wave * kQPerWave;
+  const int tile_pos = kBM / GT;          // positions per tile
+  const int q0 = qt * tile_pos;
+  const int qw0 = q0 + (wave / GT) * kQPerWave;
+  const int bh = hb + wave % GT;          // this wave's head in the key loop
 
   const char* Qb = (const char*)p.Q + (size_t)bh * T * C::kRowBytes;
-  const char* Kb = (const char*)p.Kseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
-  const char* Vb = (const char*)p.Vseq + (size_t)(b * p.Hk + g) * T * C::kRowBytes;
+  const char* Kb = (const char*)p.Kseq + (size_t)bg * T * C::kRowBytes;
+  const char* Vb = (const char*)p.Vseq + (size_t)bg * T * C::kRowBytes;
 
   const int L = p.depth_count;
   const float c2 = p.scale_log2;
@@ -443,22 +450,35 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   auto depth_phase = [&](auto MODE_T) {
     constexpr int MODE = decltype(MODE_T)::value;
     const int lane = lane_id();
-    unsigned char* xw = smem + wave * C::kXWave;
-    float* ml = (float*)(xw + 32 * C::kXRow);
     constexpr int LPR = C::kChunks;   // lanes per query row: each owns 8 channels (16 B)
     constexpr int RPS = 64 / LPR;     // query rows per wave step
-    constexpr int NIT = 32 / RPS;     // row steps of the wave's 32 queries
+    constexpr int NIT = 32 / RPS;     // row steps of the wave's 32 rows
     const int rg = lane / LPR;
     const int l16 = lane % LPR;       // owns channels 8*l16 .. 8*l16+7
     const size_t drow = (size_t)p.depth_alloc * C::kRowBytes;  // bytes of one position's slots
-    const char* Kdb = (const char*)p.Kdepth + (size_t)(b * p.Hk + g) * T * drow;
-    const char* Vdb = (const char*)p.Vdepth + (size_t)(b * p.Hk + g) * T * drow;
-    char* Ob = (char*)p.O + (size_t)bh * T * C::kRowBytes;
-    float* LSEb = p.LSE + (size_t)bh * T;
+    const char* Kdb = (const char*)p.Kdepth + (size_t)bg * T * drow;
+    const char* Vdb = (const char*)p.Vdepth + (size_t)bg * T * drow;
+    // In this phase wave w takes 32 / GT positions x all GT heads of the tile, heads fastest:
+    // the rows of one load instruction that share a position fetch the same depth slots, so a
+    // group's slots come from memory once per tile, not once per head.  A row's state lives in
+    // the exchange buffer of the wave that owns it in the key loop (hence the barriers around
+    // this phase).
+    struct Row {
+      int head;  // within the tile
+      int pos;   // within the tile
+    };
+    auto row_at = [&](int it) {
+      const int r = it * RPS + rg;
+      return Row{r % GT, wave * (kQPerWave / GT) + r / GT};
+    };
+    auto state_of = [&](Row r) { return smem + ((r.pos / kQPerWave) * GT + r.head) * C::kXWave; };
 
     // row state in the row-major mapping
     float o[8], m = 0.f, l = 1.f;
-    auto begin_row = [&](int row) {
+    auto begin_row = [&](Row rw) {
+      unsigned char* xw = state_of(rw);
+      float* ml = (float*)(xw + 32 * C::kXRow);
+      const int row = rw.pos % kQPerWave;
       if constexpr (MODE == 1) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) o[k] = 0.f;
@@ -473,7 +493,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         l = ml[2 * row + 1];
       }
     };
-    auto end_row = [&](int row) {
+    auto end_row = [&](Row rw) {
+      unsigned char* xw = state_of(rw);
+      float* ml = (float*)(xw + 32 * C::kXRow);
+      const int row = rw.pos % kQPerWave;
       if constexpr (MODE == 1) {
         *(f32x4*)(xw + row * C::kXRow + l16 * 32) = (f32x4){o[0], o[1], o[2], o[3]};
         *(f32x4*)(xw + row * C::kXRow + l16 * 32 + 16) = (f32x4){o[4], o[5], o[6], o[7]};
@@ -482,21 +505,21 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
           ml[2 * row + 1] = l;
         }
       } else {
-        const int t = qw0 + row;
+        const int t = q0 + rw.pos;
         if (t < T) {
           const float inv = 1.0f / l;
           u32x4 ov = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
                       pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
-          *(u32x4*)(Ob + (size_t)t * C::kRowBytes + l16 * 16) = ov;
-          if (l16 == 0) LSEb[t] = m * p.scale + __logf(l);
+          const size_t orow = (size_t)(hb + rw.head) * T + t;
+          *(u32x4*)((char*)p.O + orow * C::kRowBytes + l16 * 16) = ov;
+          if (l16 == 0) p.LSE[orow] = m * p.scale + __logf(l);
         }
       }
     };
     if constexpr (MODE == 2) {
       for (int it = 0; it < NIT; ++it) {
-        const int row = it * RPS + rg;
-        begin_row(row);
-        end_row(row);
+        begin_row(row_at(it));
+        end_row(row_at(it));
       }
       return;
     }
@@ -513,8 +536,9 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void*)Vdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
     auto issue = [&](int it, int c, DepthBuf& buf) {
-      const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1, never stored
-      buf.q = *(const u32x4*)(Qb + (size_t)tc * C::kRowBytes + l16 * 16);
+      const Row rw = row_at(it);
+      const int tc = min(q0 + rw.pos, T - 1);  // rows past the end use row T-1, never stored
+      buf.q = *(const u32x4*)((const char*)p.Q + ((size_t)(hb + rw.head) * T + tc) * C::kRowBytes + l16 * 16);
       const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
       // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
       // rather than fetching bytes that nothing uses
@@ -591,10 +615,9 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     // fold the current item from `cur`; false when it was the last one
     auto one = [&](const DepthBuf& cur, DepthBuf& refill) -> bool {
       issue_next(refill);
-      const int row = it * RPS + rg;
-      if (c == 0) begin_row(row);
+      if (c == 0) begin_row(row_at(it));
       fold(c, cur);
-      if (c == nch - 1) end_row(row);
+      if (c == nch - 1) end_row(row_at(it));
       advance(it, c);
       return it < NIT;
     };
@@ -620,9 +643,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const bool depth_first = L > 0 && ((blockIdx.x >> 3) & 1) != 0;
   if (depth_first) {
     depth_phase(kDepthFirst);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();  // rows were written into the buffers of the waves that own them
   }
   // From here to the release marker the accumulation registers are owned by name.
   asm volatile("; MODA_ACC_REGISTERS_ACQUIRED" ::: "memory");
@@ -667,7 +688,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   }
 
   // number of key tiles this workgroup walks, and the last one this wave needs
-  const int n_keys = p.causal ? min(T, q0 + kBM) : T;
+  const int n_keys = p.causal ? min(T, q0 + tile_pos) : T;
   const int nt = (n_keys + kBN - 1) / kBN;
   const int wave_last = p.causal ? min(nt - 1, qw0 / kBN) : nt - 1;
 
@@ -905,10 +926,8 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       ml[2 * l32] = m_run;
       ml[2 * l32 + 1] = l_tot;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
+  __syncthreads();  // the depth phase reads rows from the buffers of other waves
   // From here on the accumulation registers are the compiler's (it parks depth K/V
   // loads in them); the build step checks that on the generated code.
   asm volatile("; MODA_ACC_REGISTERS_RELEASED" ::: "memory");
@@ -923,10 +942,12 @@ namespace moda {
 int fwd_bf16_tile_rows(int waves) { return waves * kQPerWave; }
 
 hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t stream) {
-  const long long blocks = (long long)p.B * p.Hq * p.n_qtiles;
+  const int gt = p.heads_per_tile;
+  if ((waves != 4 && waves != 8) || gt < 1 || waves % gt != 0 || (p.Hq / p.Hk) % gt != 0) return hipErrorInvalidValue;
+  const int tile_pos = waves * kQPerWave / gt;
+  if (p.n_qtiles != (p.T + tile_pos - 1) / tile_pos) return hipErrorInvalidValue;
+  const long long blocks = (long long)p.B * (p.Hq / gt) * p.n_qtiles;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  if ((waves != 4 && waves != 8) || p.n_qtiles != (p.T + waves * kQPerWave - 1) / (waves * kQPerWave))
-    return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks), block(waves * 64);
   if (d == 128 && waves == 8)
     hipLaunchKernelGGL((moda_fwd_bf16_kernel<128, 8>), grid, block, 0, stream, p);
