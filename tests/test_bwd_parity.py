@@ -151,3 +151,9 @@ def test_bwd_unattended_slots_may_hold_nan(Hq, Hk, L):
         compare(name, g, r)
     assert torch.count_nonzero(grads[3][:, :, :, L:].float()) == 0
     assert torch.count_nonzero(grads[4][:, :, :, L:].float()) == 0
+
+
+def test_bwd_paper_kernel_benchmark_heads_t256():
+    """Head geometry of the paper's kernel benchmark (Hq=64, Hk=8, d=64, 64 slots) on a T=256 problem,
+    all five gradients in full."""
+    check_full(1, 64, 256, 64, 64, 29, Hk=8)

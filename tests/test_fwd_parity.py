@@ -178,3 +178,9 @@ def test_grouped_queries_many_heads(B, Hq, Hk, T, d, L):
     group land on the same die (B * Hq a multiple of 8 * group size); the paper's kernel
     benchmark shape Hq = 64, Hk = 8, d = 64 among them."""
     check_full(B, Hq, Hk, T, d, L, "bf16", 800 + Hq + T)
+
+
+def test_paper_kernel_benchmark_shape_sampled():
+    """The shape family of the paper's kernel benchmark (Table 2): B=1, Hq=64, Hk=8 (G=8), d=64,
+    64 depth slots, here at T=16384 on sampled rows of every head."""
+    check_sampled(1, 64, 8, 16384, 64, 64, "bf16", 5, n_random=12)
