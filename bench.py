@@ -33,6 +33,7 @@ WORKLOADS = {
     "copy_calibration": None,  # plain device copy of known size, for scaling the HBM byte counters
     "sweep": None,             # BASELINE configs[3]: B=4 H=16 d=128, T x depth_count grid
     "paper_table2": None,      # the paper's Table 2 shapes (d=64, grouped queries, 64..256 slots), fwd+bwd
+    "decode": None,            # one new token per sequence against a 64K sequence cache
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 vector
 
@@ -148,6 +149,33 @@ def run_paper_table2(args):
                       "steps": args.steps, "rows": rows}))
 
 
+def run_decode(args):
+    """Decoding step (one new token per sequence): bound by reading the sequence K/V cache once."""
+    from paper_2603_15619_amd import moda_attn_decode, synth
+
+    points = []
+    for (B, Hq, Hk, T, d, L) in ((8, 16, 16, 65536, 128, 15), (32, 16, 16, 4096, 128, 15), (8, 64, 8, 65536, 64, 64)):
+        inp = synth.make_inputs(B, Hq, Hk, T, d, 0, dtype="bf16", seed=6, device="cuda")
+        one = synth.make_inputs(B, Hq, Hk, 1, d, L, dtype="bf16", seed=7, device="cuda")
+        Q = one["Q"][:, :, 0].contiguous()
+        Kd, Vd = one["Kdepth"][:, :, 0].contiguous(), one["Vdepth"][:, :, 0].contiguous()
+        O = torch.empty_like(Q)
+        LSE = torch.empty((B, Hq), dtype=torch.float32, device="cuda")
+        ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        fn = lambda: moda_attn_decode(Q, inp["Kseq"], inp["Vseq"], Kd, Vd, out=O, lse=LSE, workspace=ws)
+        ms, ms_k, _ = time_calls(fn, args.steps, args.warmup)
+        cache_bytes = 2.0 * B * Hk * T * d * 2
+        points.append({"B": B, "Hq": Hq, "Hk": Hk, "T": T, "d": d, "depth_count": L, "ms": round(ms, 4),
+                       "cache_GB": round(cache_bytes / 1e9, 3),
+                       "hbm_gbps": round(cache_bytes / (ms_k * 1e-3) / 1e9, 1),
+                       "frac_of_8TBps": round(cache_bytes / (ms_k * 1e-3) / 1e9 / 8000.0, 4),
+                       "tokens_per_s": round(B / (ms * 1e-3), 1)})
+        del inp
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "MoDA attn decoding step (2 kernels per call), bf16", "steps": args.steps,
+                      "warmup": args.warmup, "points": points}))
+
+
 def run_backward(args, B, Hq, Hk, T, d, L, dtype):
     from paper_2603_15619_amd import moda_attn_bwd, moda_attn_fwd, synth
 
@@ -247,6 +275,8 @@ def main():
         return run_sweep(args)
     if args.workload == "paper_table2":
         return run_paper_table2(args)
+    if args.workload == "decode":
+        return run_decode(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
     if args.depth_count is not None:
         L = args.depth_count

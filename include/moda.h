@@ -124,6 +124,26 @@ moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, con
 moda_status moda_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, int32_t slot,
                               const moda_shape* s, void* hip_stream);
 
+/*
+ * Decoding step: ONE new token per sequence (paper Table 1, "Decoding" rows).  The
+ * operator is the one defined above for the query at the last position: it attends
+ * the T positions [0, T) of the sequence cache (the new token's own key/value, which
+ * the caller has already written at position T-1, included; no mask is needed) and
+ * the depth_count depth slots of ITS OWN position, under one softmax.  During
+ * decoding the depth cache therefore holds one position only.
+ *   in : Q                 [B, Hq, d]              the new token's queries
+ *        Kseq, Vseq        [B, Hk, kv_alloc, d]    sequence cache, kv_alloc >= T rows allocated
+ *        Kdepth, Vdepth    [B, Hk, depth_alloc, d] the new token's depth slots (NULL iff depth_count == 0)
+ *   out: O                 [B, Hq, d], LSE [B, Hq] fp32
+ *   workspace: device scratch of at least moda_attn_decode_workspace_bytes(s) bytes
+ *        (partial results of the slices the sequence is split into), 16-byte aligned.
+ * `s->T` is the attended length (>= 1), `s->causal` is ignored.  bf16 only.
+ */
+size_t moda_attn_decode_workspace_bytes(const moda_shape* s);
+moda_status moda_attn_decode(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                             const void* Vdepth, void* O, float* LSE, int32_t kv_alloc, void* workspace,
+                             size_t workspace_bytes, const moda_shape* s, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* moda_status_string(moda_status st);
 

@@ -15,6 +15,7 @@ LIB_PATH = os.environ.get("MODA_LIB_PATH") or os.path.join(HERE, "libmoda.so")
 
 MODA_F32, MODA_BF16 = 0, 1
 EXPORTS = ("moda_attn_fwd", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd", "moda_depth_append",
+           "moda_attn_decode", "moda_attn_decode_workspace_bytes",
            "moda_status_string", "moda_version", "moda_kernels_per_call")
 
 
@@ -52,6 +53,10 @@ def lib():
         L.moda_attn_bwd.restype = ctypes.c_int
         L.moda_depth_append.argtypes = [vp, vp, vp, vp, ctypes.c_int32, sp, vp]
         L.moda_depth_append.restype = ctypes.c_int
+        L.moda_attn_decode_workspace_bytes.argtypes = [sp]
+        L.moda_attn_decode_workspace_bytes.restype = ctypes.c_size_t
+        L.moda_attn_decode.argtypes = [vp] * 7 + [ctypes.c_int32, vp, ctypes.c_size_t, sp, vp]
+        L.moda_attn_decode.restype = ctypes.c_int
         L.moda_status_string.argtypes = [ctypes.c_int]
         L.moda_status_string.restype = ctypes.c_char_p
         L.moda_version.restype = ctypes.c_int
@@ -186,3 +191,37 @@ def moda_depth_append(K, V, Kdepth, Vdepth, slot):
         _check(lib().moda_depth_append(_ptr(K), _ptr(V), _ptr(Kdepth), _ptr(Vdepth), int(slot),
                                        ctypes.byref(s), _stream(dev)))
     return Kdepth, Vdepth
+
+
+def moda_attn_decode(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, T=None, depth_count=None, scale=None,
+                     out=None, lse=None, workspace=None):
+    """O [B,Hq,d], LSE [B,Hq] for one new token per sequence: Q [B,Hq,d]; sequence cache
+    Kseq/Vseq [B,Hk,kv_alloc,d] of which positions [0, T) are attended (default: all); the new
+    token's depth slots Kdepth/Vdepth [B,Hk,depth_alloc,d] or None."""
+    B, Hq, d = Q.shape
+    Hk, kv_alloc = Kseq.shape[1], Kseq.shape[2]
+    T = kv_alloc if T is None else int(T)
+    La = 0 if Kdepth is None else Kdepth.shape[2]
+    L = La if depth_count is None else int(depth_count)
+    dev, dt = Q.device, Q.dtype
+    _require(Q, "Q", (B, Hq, d), dt, dev)
+    _require(Kseq, "Kseq", (B, Hk, kv_alloc, d), dt, dev)
+    _require(Vseq, "Vseq", (B, Hk, kv_alloc, d), dt, dev)
+    _require(Kdepth, "Kdepth", (B, Hk, La, d), dt, dev)
+    _require(Vdepth, "Vdepth", (B, Hk, La, d), dt, dev)
+    s = MODAShape(B, Hq, Hk, T, d, La, L, 1, float(scale) if scale else 0.0, _dtype_code(Q))
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+    _require(out, "out", Q.shape, dt, dev)
+    _require(lse, "lse", (B, Hq), torch.float32, dev)
+    need = int(lib().moda_attn_decode_workspace_bytes(ctypes.byref(s)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().moda_attn_decode(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth), _ptr(out),
+                                      _ptr(lse), int(kv_alloc), _ptr(workspace), ws_bytes, ctypes.byref(s),
+                                      _stream(dev)))
+    return out, lse

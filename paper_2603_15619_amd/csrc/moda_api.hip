@@ -126,6 +126,32 @@ moda_status moda_depth_append(const void* K, const void* V, void* Kdepth, void* 
   return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
 }
 
+size_t moda_attn_decode_workspace_bytes(const moda_shape* s) {
+  if (check_shape(s) != MODA_OK || s->dtype != MODA_BF16 || s->B == 0 || s->T == 0) return 0;
+  return moda::decode_workspace_bytes(s->B, s->Hq, s->Hk, s->T, s->d);
+}
+
+moda_status moda_attn_decode(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                             const void* Vdepth, void* O, float* LSE, int32_t kv_alloc, void* workspace,
+                             size_t workspace_bytes, const moda_shape* s, void* hip_stream) {
+  moda_status st = check_shape(s);
+  if (st != MODA_OK) return st;
+  if (s->dtype != MODA_BF16) return MODA_ERR_UNSUPPORTED;
+  if (s->T < 1 || kv_alloc < s->T) return MODA_ERR_SHAPE;  // the new token's own key is always attended
+  if ((unsigned long long)kv_alloc * (unsigned long long)s->d * 2ull >= (1ull << 32)) return MODA_ERR_UNSUPPORTED;
+  if (s->B == 0) return MODA_OK;
+  if (!Q || !Kseq || !Vseq || !O || !LSE) return MODA_ERR_NULL;
+  if (s->depth_count > 0 && (!Kdepth || !Vdepth)) return MODA_ERR_NULL;
+  const void* ptrs[] = {Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, workspace};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MODA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < moda_attn_decode_workspace_bytes(s)) return MODA_ERR_WORKSPACE;
+  hipError_t e = moda::launch_decode_bf16(Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, static_cast<float*>(workspace),
+                                          s->B, s->Hq, s->Hk, s->T, kv_alloc, s->d, s->depth_alloc, s->depth_count,
+                                          resolve_scale(s), static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
+}
+
 size_t moda_attn_bwd_workspace_bytes(const moda_shape* s) {
   if (check_shape(s) != MODA_OK) return 0;
   moda::BwdParams p{};

@@ -21,4 +21,12 @@ hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream);
 hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, long long rows,
                                int row_bytes, int depth_alloc, int slot, hipStream_t stream);
 
+// Decoding step (one new token per sequence), bf16: partial kernel over slices of the sequence
+// cache + merge kernel; `ws` holds decode_workspace_bytes(...) bytes.
+size_t decode_workspace_bytes(int B, int Hq, int Hk, int T, int d);
+hipError_t launch_decode_bf16(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                              const void* Vdepth, void* O, float* LSE, float* ws, int B, int Hq, int Hk, int T,
+                              int T_alloc, int d, int depth_alloc, int depth_count, float scale,
+                              hipStream_t stream);
+
 }  // namespace moda
