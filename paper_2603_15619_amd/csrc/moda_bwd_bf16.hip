@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   const int l32 = lane & 31, hi = lane >> 5;
   const int T = p.T;
   const int BHk = p.B * p.Hk;
-  const int bg = blockIdx.x % BHk;  // (batch, key/value head)
-  const int jt = blockIdx.x / BHk;  // key tiles in natural order: the first ones see the most queries
+  int bg, jt;  // (batch, key/value head); key tiles in natural order: the first ones see the most queries
+  head_blocked_id((int)blockIdx.x, BHk, (T + 127) / 128, bg, jt);
   const int j0 = jt * 128;
   const int kw0 = j0 + wave * 32;
   const int G = p.Hq / p.Hk;        // query heads per key/value head: their gradients add up here
@@ -239,9 +239,10 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int l32 = lane & 31, hi = lane >> 5;
   const int T = p.T;
   const int BH = p.B * p.Hq;
-  const int bh = blockIdx.x % BH;
   const int n_qt = (T + 127) / 128;
-  const int qt = n_qt - 1 - blockIdx.x / BH;  // heavy (late) query tiles first
+  int bh, tile_idx;
+  head_blocked_id((int)blockIdx.x, BH, n_qt, bh, tile_idx);
+  const int qt = n_qt - 1 - tile_idx;  // heavy (late) query tiles first
   const int q0 = qt * 128;
   const int qw0 = q0 + wave * 32;
   const int G = p.Hq / p.Hk;
