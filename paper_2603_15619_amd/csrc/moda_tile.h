@@ -1,9 +1,22 @@
 // LDS tile helpers shared by the backward kernels (gfx950).
 //
-// A tile is 64 rows x D channels of bf16, row-major, with its 32-byte pairs of
-// 16-byte chunks permuted by an XOR with the row index: the pair p of row r sits at
-// pair position p ^ (r & (pairs-1)).  Both access patterns used below are then
-// spread over the LDS banks:
+// A tile is 64 rows x D channels of bf16, row-major, with the 16-byte chunks of a row
+// permuted by an XOR with a function of the row index: chunk c of row r sits at chunk
+// position c ^ swz(r).  For both access patterns used below to touch every LDS bank once
+// (64 banks x 4 bytes = 256 bytes per cycle):
+//   - a row-fragment read takes the same logical chunk of 16 consecutive rows: swz must
+//     give those rows 16 different (half-of-256-bytes, chunk position) places;
+//   - a transposing read takes, per cycle, one 64-byte segment (4 chunks) of 4 consecutive
+//     rows: swz must send those rows to different 64-byte bank groups, i.e. differ in its
+//     bit 2 (and bit 3 at d = 128) among them.
+//   d = 64  ( 8 chunks, two rows = all banks): swz(r) = (((r >> 1) & 1) << 2) | ((r >> 2) & 3)
+//           meets both (measured: bank-conflict cycles 50-66 % -> 0, kernels 3-13 % faster).
+//   d = 128 (16 chunks, a row = all banks): ((r & 3) << 2) | ((r >> 2) & 3) meets both as well,
+//           but the rows r and r + 8 of a transposed fragment then differ in their permutation,
+//           which costs the dK/dV kernel four more address registers than it has (measured:
+//           conflicts 43 % -> 0, yet 1.78 -> 2.03 ms because of spills).  It keeps
+//           swz(r) = (r & 7) << 1, a 2-way conflict on both patterns.
+// The access patterns:
 //   row fragment  (MFMA A operand, M = rows, K = channels): lane l reads 16 bytes of
 //                 row (l % 32), channels 16*st + 8*(l/32) .. +7;
 //   transposed fragment (MFMA A operand, M = channels, K = rows), built from two
@@ -31,11 +44,11 @@ struct Tile {
   static constexpr int kDSteps = D / 16;
   static constexpr int kDBlocks = D / 32;
 
-  // byte offset of the 16-byte chunk c of row r
-  __device__ static __forceinline__ int off(int r, int c) {
-    const int pair = (c >> 1) ^ (r & (kChunks / 2 - 1));
-    return r * kRowBytes + (pair << 5) + ((c & 1) << 4);
+  __device__ static __forceinline__ int swz(int r) {
+    return D == 128 ? ((r & 7) << 1) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
   }
+  // byte offset of the 16-byte chunk c of row r
+  __device__ static __forceinline__ int off(int r, int c) { return r * kRowBytes + ((c ^ swz(r)) << 4); }
   // row fragment: rows rb*32 .. rb*32+31, channel step st
   __device__ static __forceinline__ bf16x8 row_frag(const unsigned char* tile, int rb, int st, int lane) {
     const int l32 = lane & 31, hi = lane >> 5;
@@ -45,10 +58,19 @@ struct Tile {
   __device__ static __forceinline__ bf16x8 tr_frag(const unsigned char* tile, int ks, int db, int lane) {
     const int hi = lane >> 5;
     const int rr = ks * 16 + hi * 4 + ((lane & 15) >> 2);
-    const int ch = db * 4 + ((lane >> 4) & 1) * 2;
-    const int sub = (lane & 3) * 8;
-    const unsigned char* a0 = tile + off(rr, ch) + sub;
-    const unsigned char* a1 = tile + off(rr + 8, ch) + sub;
+    // this lane's 8 bytes: piece (lane & 3) of the two chunks of a 16-channel block.  At
+    // d = 128 the permutation keeps the two chunks adjacent and the rows r, r + 8 alike (one
+    // address computation serves both); at d = 64 chunks are permuted one by one.
+    const unsigned char *a0, *a1;
+    if constexpr (D == 128) {
+      const int ch = db * 4 + ((lane >> 4) & 1) * 2;
+      a0 = tile + off(rr, ch) + (lane & 3) * 8;
+      a1 = a0 + 8 * kRowBytes;
+    } else {
+      const int ch = db * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+      a0 = tile + off(rr, ch) + (lane & 1) * 8;
+      a1 = tile + off(rr + 8, ch) + (lane & 1) * 8;
+    }
     s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
     s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a1);
     s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -82,7 +104,7 @@ struct TileLoader {
     for (int i = 0; i < kInstPerWave; ++i) {
       const int r = (wave * kInstPerWave + i) * kRowsPerInst + lane / Tile<D>::kChunks;
       const int pc = lane % Tile<D>::kChunks;  // chunk position this lane fills
-      const int c = (((pc >> 1) ^ (r & (Tile<D>::kChunks / 2 - 1))) << 1) | (pc & 1);
+      const int c = pc ^ Tile<D>::swz(r);
       row[i] = r;
       goff[i] = r * Tile<D>::kRowBytes + c * 16;
     }
