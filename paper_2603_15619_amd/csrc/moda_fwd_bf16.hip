@@ -183,8 +183,9 @@ __device__ __forceinline__ void wait_copies_but() {  // all but the N most recen
 //           chunk (c ^ row) & 3: 16 different 16-byte bank groups, conflict free.  Because
 //           only two chunk bits depend on the lane, the address of fragment (st, kb) is one
 //           of TWO per-lane registers (st even / odd) plus an immediate.
-//   K tile, d = 64:  chunk c of row r at chunk position c ^ (r & 7), pieces adjacent; one
-//           per-lane register per k-step.
+//   K tile, d = 64:  chunk c of row r at chunk position c ^ ((r >> 1) & 7), pieces adjacent
+//           (two 128-byte rows span the banks, so 16 consecutive rows need 8 different
+//           positions per row parity); one per-lane register per k-step.
 //   V tile: the 64-byte segment (c >> 2) sits at segment position (c >> 2) ^ vswz(r).  The
 //           transposing read takes 2 cycles of 32 lanes; in one cycle the lanes read 4
 //           consecutive rows x one 64-byte segment, and vswz spreads those 4 rows over the
@@ -205,7 +206,7 @@ struct FragBase {
 #pragma unroll
       for (int e = 0; e < 2; ++e) k[e] = smem_addr + kbase + ((((e << 1) | hi) ^ j) << 4);
     } else {
-      const int kbase = l32 * C::kRowBytes + (((l32 & (C::kChunks - 1)) ^ hi) << 4);
+      const int kbase = l32 * C::kRowBytes + ((((l32 >> 1) & (C::kChunks - 1)) ^ hi) << 4);
 #pragma unroll
       for (int st = 0; st < C::kDSteps; ++st) k[st] = smem_addr + (kbase ^ (st << 5));
     }
@@ -694,15 +695,17 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
   // ---- global -> LDS copies of one K or V tile.  One wave instruction moves one 1 KB
   // piece, so the chunk permutation is applied by choosing which global chunk each lane
-  // fetches; it is the same for every piece (the permutations only look at the row index
-  // inside a piece), so one per-lane offset serves all K copies and one all V copies.
+  // fetches; one per-lane offset serves all K copies and one all V copies (at d = 128 the
+  // permutations only look at the row index inside a piece; at d = 64 the K permutation also
+  // looks at the parity of the piece, a constant XOR for a wave's odd pieces).
   // A wave copies pieces wave * kInstPerWave + i, i < kInstPerWave, of every tile.
   int k_goff, v_goff;
   {
     const int lane = tid & 63;
     const int j = lane / C::kChunks;   // row inside the piece
     const int pc = lane % C::kChunks;  // chunk position this lane fills
-    const int kc = C::kD == 128 ? (pc ^ (j & 3)) : (pc ^ (j & (C::kChunks - 1)));
+    const int piece0 = wave * C::kInstPerWave;  // the wave's first piece
+    const int kc = C::kD == 128 ? (pc ^ (j & 3)) : (pc ^ ((((piece0 & 1) * C::kPieceRows + j) >> 1) & (C::kChunks - 1)));
     const int vc = (((pc >> 2) ^ C::vswz(j)) << 2) | (pc & 3);
     k_goff = j * C::kRowBytes + kc * 16;
     v_goff = j * C::kRowBytes + vc * 16;
@@ -725,9 +728,16 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     constexpr int i = decltype(I)::value;
     constexpr int stride = is_k ? C::kKPieceStride : C::kVPieceStride;
     const int soff = __builtin_amdgcn_readfirstlane(kt * C::kGTileBytes) + wave_goff;
+    int goff = is_k ? k_goff : v_goff;
+    if constexpr (is_k && C::kD == 64 && (i & 1) != 0) {
+      // odd piece of an even first piece (kInstPerWave is even whenever it is not 1): the row
+      // index has bit 3 set, which flips bit 2 of the chunk permutation
+      static_assert(C::kInstPerWave % 2 == 0, "a wave's first piece is even");
+      asm volatile("v_xor_b32 %0, %1, %2" : "=v"(goff) : "n"(4 << 4), "v"(k_goff));
+    }
     copy16_to_lds<decltype(STAGE_OFF)::value + i * (stride - 1024), i * 1024,
                   is_k ? 0 : -(kStages - C::kVAhead) * C::kGTileBytes>(
-        buf, is_k ? k_goff : v_goff, soff, is_k ? wave_lds : wave_lds_v);
+        buf, goff, soff, is_k ? wave_lds : wave_lds_v);
   };
   auto issue_tile = [&](auto IS_K, auto STAGE_OFF, const i32x4& buf, int kt) {
     static_for<C::kInstPerWave>([&](auto I) { issue_one(IS_K, I, STAGE_OFF, buf, kt); });
