@@ -67,39 +67,63 @@ __global__ __launch_bounds__(kDecWaves * 64) void moda_decode_partial_kernel(Dec
   const char* Kb = (const char*)p.Kseq + (size_t)bg * p.T_alloc * RB + l16 * 16;
   const char* Vb = (const char*)p.Vseq + (size_t)bg * p.T_alloc * RB + l16 * 16;
 
-  // this lane's keys: k_begin + (wave * RPS + rg) + i * (kDecWaves * RPS); two key rows in flight
+  // this lane's keys: k_begin + (wave * RPS + rg) + i * (kDecWaves * RPS), kU at a time with the
+  // next kU in flight; the running max is raised (and the state rescaled) once per kU keys
   constexpr int STEP = kDecWaves * RPS;
-  int key = k_begin + wave * RPS + rg;
+  constexpr int kU = 4;
+  const int key0 = k_begin + wave * RPS + rg;
   auto load = [&](const char* base, int kk) {
     return __builtin_nontemporal_load((const u32x4*)(base + (size_t)min(kk, p.T - 1) * RB));
   };
-  u32x4 kn = load(Kb, key), vn = load(Vb, key);
-  for (; key - rg - wave * RPS < k_end; key += STEP) {  // uniform trip count over the workgroup
-    const u32x4 kv = kn, vv = vn;
-    kn = load(Kb, key + STEP);
-    vn = load(Vb, key + STEP);
-    const bool live = key < k_end;
-    float vx[8];
+  u32x4 kn[kU], vn[kU];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      vx[2 * k] = bf16_lo(vv[k]);
-      vx[2 * k + 1] = bf16_hi(vv[k]);
+  for (int u = 0; u < kU; ++u) {
+    kn[u] = load(Kb, key0 + u * STEP);
+    vn[u] = load(Vb, key0 + u * STEP);
+  }
+  for (int base = k_begin; base < k_end; base += kU * STEP) {  // uniform trip count over the workgroup
+    const int key = key0 + (base - k_begin);
+    u32x4 kv[kU], vv[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      kv[u] = kn[u];
+      vv[u] = vn[u];
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      kn[u] = load(Kb, key + (kU + u) * STEP);
+      vn[u] = load(Vb, key + (kU + u) * STEP);
     }
 #pragma unroll
     for (int j = 0; j < GT; ++j) {
-      float sc = 0.f;
+      float sc[kU];
+      float mn = m[j];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) sc = dot2_bf16(q[j][k], kv[k], sc);
-      sc = group_sum<LPR>(sc);
-      sc = live ? sc : -INFINITY;
-      const float mn = fmaxf(m[j], sc);
+      for (int u = 0; u < kU; ++u) {
+        float a = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a = dot2_bf16(q[j][k], kv[u][k], a);
+        a = group_sum<LPR>(a);
+        sc[u] = key + u * STEP < k_end ? a : -INFINITY;
+        mn = fmaxf(mn, sc[u]);
+      }
       // (mn is -inf only while every key so far was past the slice: then nothing is added)
-      const float al = mn == -INFINITY ? 0.f : fast_exp2((m[j] - mn) * c2);
-      const float pw = mn == -INFINITY ? 0.f : fast_exp2((sc - mn) * c2);
+      const bool none = mn == -INFINITY;
+      const float al = none ? 0.f : fast_exp2((m[j] - mn) * c2);
       m[j] = mn;
-      l[j] = l[j] * al + pw;
+      l[j] *= al;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) o[j][k] = o[j][k] * al + pw * vx[k];
+      for (int k = 0; k < 8; ++k) o[j][k] *= al;
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const float pw = none ? 0.f : fast_exp2((sc[u] - mn) * c2);
+        l[j] += pw;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          o[j][2 * k] += pw * bf16_lo(vv[u][k]);
+          o[j][2 * k + 1] += pw * bf16_hi(vv[u][k]);
+        }
+      }
     }
   }
 
@@ -236,7 +260,7 @@ hipError_t launch_decode_bf16(const void* Q, const void* Kseq, const void* Vseq,
   p.B = B; p.Hq = Hq; p.Hk = Hk; p.T = T; p.T_alloc = T_alloc;
   p.depth_alloc = depth_alloc; p.depth_count = depth_count;
   p.n_split = decode_splits(B, Hk, T);
-  // slices are multiples of the 16 or 32 key rows a workgroup takes per step
+  // slices are multiples of the key rows a workgroup takes per step (16 or 32)
   const int step = kDecWaves * (64 / (d / 8));
   p.keys_per_split = ((T + p.n_split - 1) / p.n_split + step - 1) / step * step;
   p.scale = scale;
