@@ -172,6 +172,15 @@ def test_unattended_slots_may_hold_nan(L):
     assert np.abs(synth.to_f64(LSE) - Lref).max() <= TOL["bf16"][1]
 
 
+@pytest.mark.parametrize("B,Hq,Hk,T,d,L,causal", [(1, 6, 2, 300, 128, 4, True), (2, 3, 1, 200, 64, 2, True),
+                                                  (1, 12, 2, 257, 128, 7, True), (1, 8, 1, 300, 128, 3, False),
+                                                  (1, 4, 1, 70, 64, 5, False), (1, 16, 1, 100, 128, 1, True)])
+def test_grouped_queries_group_sizes(B, Hq, Hk, T, d, L, causal):
+    """Group sizes 3, 6 (tiles of 1 and 2 heads), 4, 8 (one tile per group), 16 (two tiles of 8
+    heads per group), causal and not; sequence lengths shorter and longer than a tile's positions."""
+    check_full(B, Hq, Hk, T, d, L, "bf16", 850 + Hq + T, causal=causal)
+
+
 @pytest.mark.parametrize("B,Hq,Hk,T,d,L", [(1, 16, 8, 300, 64, 3), (2, 32, 4, 260, 128, 5), (1, 64, 8, 130, 64, 9)])
 def test_grouped_queries_many_heads(B, Hq, Hk, T, d, L):
     """Head counts at which the kernel re-maps workgroup ids so that the query heads of one
