@@ -90,11 +90,12 @@ __device__ __forceinline__ void tile_copy16(const char* gbase, int voff, unsigne
 __device__ __forceinline__ void wait_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Copies rows [row0, row0+64) of a [n_rows, D] bf16 matrix into a tile; rows past
-// n_rows re-read the last row (callers mask them).  All 256 threads take part.
-template <int D>
+// n_rows re-read the last row (callers mask them).  All NW waves of the workgroup take part.
+template <int D, int NW = 4>
 struct TileLoader {
   static constexpr int kRowsPerInst = 64 / Tile<D>::kChunks;
-  static constexpr int kInstPerWave = 64 / kRowsPerInst / 4;
+  static constexpr int kInstPerWave = 64 / kRowsPerInst / NW;
+  static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
   int goff[kInstPerWave];
   int row[kInstPerWave];
   int wave;
