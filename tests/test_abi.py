@@ -68,3 +68,46 @@ def test_shape_errors_without_gpu(L):
                            ctypes.byref(MODAShape(**ok)), None) == 1  # NULL tensors
     assert fwd(MODAShape(**dict(ok, B=0))) == 0           # empty problem: nothing launched
     assert fwd(MODAShape(**dict(ok, T=0))) == 0
+
+
+def test_new_entry_points_reject_bad_arguments_without_gpu(L):
+    """moda_depth_append, moda_attn_decode and moda_attn_bwd validate everything on the host
+    before any kernel is launched."""
+    from paper_2603_15619_amd.binding import MODAShape
+
+    ok = dict(B=1, Hq=4, Hk=2, T=16, d=128, depth_alloc=3, depth_count=2, causal=1, scale=0.0, dtype=1)
+    p, bad = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+
+    def append(shape, slot, a=p):
+        return L.moda_depth_append(a, p, p, p, slot, ctypes.byref(shape), None)
+
+    assert append(MODAShape(**ok), 3) == 2                 # slot >= depth_alloc
+    assert append(MODAShape(**ok), -1) == 2
+    assert append(MODAShape(**ok), 0, a=None) == 1
+    assert append(MODAShape(**ok), 0, a=bad) == 4
+    assert append(MODAShape(**dict(ok, T=0)), 0) == 0      # empty: nothing launched
+    assert append(MODAShape(**dict(ok, depth_alloc=0, depth_count=0)), 0) == 2
+
+    def decode(shape, kv_alloc, ws=p, ws_bytes=1 << 30, q=p):
+        return L.moda_attn_decode(q, p, p, p, p, p, p, kv_alloc, ws, ws_bytes, ctypes.byref(shape), None)
+
+    need = L.moda_attn_decode_workspace_bytes(ctypes.byref(MODAShape(**ok)))
+    assert need > 0
+    assert decode(MODAShape(**ok), 15) == 2                # cache shorter than the attended length
+    assert decode(MODAShape(**dict(ok, T=0)), 16) == 2     # the new token's own key is always attended
+    assert decode(MODAShape(**dict(ok, dtype=0)), 16) == 3  # bf16 only
+    assert decode(MODAShape(**ok), 16, ws=None) == 6
+    assert decode(MODAShape(**ok), 16, ws_bytes=need - 1) == 6
+    assert decode(MODAShape(**ok), 16, q=None) == 1
+    assert decode(MODAShape(**ok), 16, q=bad) == 4
+    assert decode(MODAShape(**dict(ok, B=0)), 16) == 0
+
+    def bwd(shape, ws_bytes=1 << 30):
+        return L.moda_attn_bwd(*([p] * 14), ws_bytes, ctypes.byref(shape), None)
+
+    assert bwd(MODAShape(**dict(ok, Hq=32, Hk=2))) == 3    # more than 8 query heads per key/value head
+    assert bwd(MODAShape(**dict(ok, dtype=0))) == 3
+    assert bwd(MODAShape(**ok), ws_bytes=8) == 6
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 1) == 4               # grouped queries + depth slots
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=2))), 1) == 3
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 0) == 1
