@@ -98,7 +98,7 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
  *        gradient slots >= depth_count are written as zero
  *   workspace: device scratch of at least moda_attn_bwd_workspace_bytes(s)
  *        bytes, 16-byte aligned; contents on entry are ignored.
- * This build: bf16 only, Hq / Hk <= 8 (else MODA_ERR_UNSUPPORTED).
+ * This build: bf16 only, Hq / Hk <= 64 (else MODA_ERR_UNSUPPORTED).
  */
 size_t moda_attn_bwd_workspace_bytes(const moda_shape* s);
 moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,

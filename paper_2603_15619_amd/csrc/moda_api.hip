@@ -67,7 +67,8 @@ int moda_kernels_per_call(const moda_shape* s, int which) {
   if (check_shape(s) != MODA_OK || s->B == 0 || s->T == 0) return 0;
   if (which == 0) return 1;
   if (s->dtype != MODA_BF16 || s->Hq / s->Hk > moda::bwd_bf16_max_group()) return 0;
-  return (s->Hq != s->Hk && s->depth_alloc > 0) ? 4 : 3;
+  const int G = s->Hq / s->Hk;
+  return 3 + ((G > 1 && s->depth_alloc > 0) ? (G + 7) / 8 : 0);
 }
 
 moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,

@@ -17,7 +17,7 @@
 //            dQ^T += K^T dS^T; then, in a row-major epilogue, the depth slots of the
 //            query's own position give dKdepth, dVdepth (row-local, written once)
 //            and their share of dQ.
-// Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 8): the
+// Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 64): the
 // gradients of the shared keys and values sum over the group.  dkdv walks the query
 // tiles of all G heads; the depth-slot gradients move from the dq kernel's epilogue to a
 // kernel of their own (depth_gqa) that holds the G heads of a position side by side.
@@ -600,8 +600,11 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 // depth share of dQ); the row's slots stream by, one prefetched ahead.  Per slot i:
 //   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (one rounding each),
 //   dQ_h     += e_{h,i} k_i          (left in the dQ buffer, unscaled, for the dQ kernel).
+// Groups of more than GT = 8 heads take one launch per 8 heads (`head0` = first head of the
+// launch within its group); every launch after the first adds to the dKdepth / dVdepth the
+// previous ones wrote (read, add in fp32, round again).
 template <int D, int GT>
-__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
+__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p, int head0) {
   constexpr int LPR = D / 8, ROWS = 256 / LPR, RB = D * 2;
   const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
   const int tid = threadIdx.x, l16 = tid % LPR;
@@ -618,7 +621,7 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
   float l2[GT], dl[GT], dq[GT][8];
 #pragma unroll
   for (int j = 0; j < GT; ++j) {
-    const int bh = bh0 + min(j, G - 1);  // heads past the group repeat the last one with weight zero
+    const int bh = bh0 + min(head0 + j, G - 1);  // heads past the group repeat the last one with weight zero
     q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
     g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
     l2[j] = p.LSE[(size_t)bh * T + t] * kLog2e;
@@ -660,7 +663,7 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
       }
       sdot = group_sum<LPR>(sdot);
       gdot = group_sum<LPR>(gdot);
-      const float pe = j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
+      const float pe = head0 + j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
       const float e = pe * (gdot - dl[j]);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -674,6 +677,16 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
     }
     if (live) {
       const float f = p.scale;
+      if (head0 > 0) {  // add what the launches for the heads before wrote (already scaled)
+        const u32x4 pv = *(const u32x4*)(dvd + (size_t)i * RB), pk = *(const u32x4*)(dkd + (size_t)i * RB);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          av[2 * k] += bf16_lo(pv[k]);
+          av[2 * k + 1] += bf16_hi(pv[k]);
+          ak[2 * k] += bf16_lo(pk[k]) / f;
+          ak[2 * k + 1] += bf16_hi(pk[k]) / f;
+        }
+      }
       const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
       const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
                         pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
@@ -683,16 +696,16 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
   }
   if (live) {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
+    for (int i = L; i < La && head0 == 0; ++i) {  // allocated but unattended slots get zero gradients
       *(u32x4*)(dvd + (size_t)i * RB) = z;
       *(u32x4*)(dkd + (size_t)i * RB) = z;
     }
 #pragma unroll
     for (int j = 0; j < GT; ++j)
-      if (j < G) {
+      if (head0 + j < G) {
         const u32x4 ov = {pack_bf16(dq[j][0], dq[j][1]), pack_bf16(dq[j][2], dq[j][3]),
                           pack_bf16(dq[j][4], dq[j][5]), pack_bf16(dq[j][6], dq[j][7])};
-        *(u32x4*)((char*)p.dQ + ((size_t)(bh0 + j) * T + t) * RB + l16 * 16) = ov;
+        *(u32x4*)((char*)p.dQ + ((size_t)(bh0 + head0 + j) * T + t) * RB + l16 * 16) = ov;
       }
   }
 }
@@ -700,7 +713,7 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p) {
 // ---------------------------------------------------------------- launchers
 size_t bwd_bf16_workspace_bytes(const BwdParams& p) { return (size_t)p.B * p.Hq * p.T * sizeof(float); }
 
-int bwd_bf16_max_group() { return 8; }
+int bwd_bf16_max_group() { return 64; }
 
 template <int D>
 static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
@@ -718,11 +731,12 @@ static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
   hipLaunchKernelGGL(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.delta, rows);
   if (G > 1 && p.depth_alloc > 0) {
     if (G <= 2)
-      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 2>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 2>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, 0);
     else if (G <= 4)
-      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 4>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 4>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, 0);
     else
-      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 8>), dim3((unsigned)g_depth), dim3(256), 0, stream, p);
+      for (int head0 = 0; head0 < G; head0 += 8)
+        hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 8>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, head0);
   }
   hipLaunchKernelGGL(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), 0, stream, p);
   hipLaunchKernelGGL((moda_bwd_dq_kernel<D, kDqWaves>), dim3((unsigned)g_dq), dim3(kDqWaves * 64), 0, stream, p);

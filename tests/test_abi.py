@@ -105,9 +105,10 @@ def test_new_entry_points_reject_bad_arguments_without_gpu(L):
     def bwd(shape, ws_bytes=1 << 30):
         return L.moda_attn_bwd(*([p] * 14), ws_bytes, ctypes.byref(shape), None)
 
-    assert bwd(MODAShape(**dict(ok, Hq=32, Hk=2))) == 3    # more than 8 query heads per key/value head
+    assert bwd(MODAShape(**dict(ok, Hq=256, Hk=2))) == 3   # more than 64 query heads per key/value head
     assert bwd(MODAShape(**dict(ok, dtype=0))) == 3
     assert bwd(MODAShape(**ok), ws_bytes=8) == 6
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 1) == 4               # grouped queries + depth slots
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 6  # 20 heads per group: 3 launches of 8
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=2))), 1) == 3
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 0) == 1

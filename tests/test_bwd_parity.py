@@ -80,17 +80,18 @@ def test_bwd_deterministic():
 def test_bwd_rejects_unsupported():
     from paper_2603_15619_amd import MODAError
 
-    inp = synth.make_inputs(1, 16, 1, 64, 128, 2, dtype="bf16", seed=25, device="cuda", with_dO=True)
-    with pytest.raises(MODAError):  # more than 8 query heads per key/value head
+    inp = synth.make_inputs(1, 128, 1, 64, 128, 2, dtype="bf16", seed=25, device="cuda", with_dO=True)
+    with pytest.raises(MODAError):  # more than 64 query heads per key/value head
         run_gpu(inp, 2)
 
 
 @pytest.mark.parametrize("Hq,Hk,T,d,L,La", [(4, 2, 300, 128, 5, None), (8, 1, 200, 64, 3, 4), (6, 2, 257, 128, 0, 2),
-                                            (8, 2, 130, 64, 9, None), (2, 1, 64, 128, 0, 0), (16, 2, 500, 64, 17, None)])
+                                            (8, 2, 130, 64, 9, None), (2, 1, 64, 128, 0, 0), (16, 2, 500, 64, 17, None),
+                                            (16, 1, 200, 128, 5, 7), (24, 1, 130, 64, 3, None), (12, 1, 257, 128, 4, None)])
 def test_bwd_grouped_queries(Hq, Hk, T, d, L, La):
     """G = Hq / Hk query heads share a key/value head: the gradients of the shared sequence
-    and depth keys / values sum over the group (G = 2, 3, 4, 8; the paper's models use G = 2,
-    its kernel benchmarks G = 8)."""
+    and depth keys / values sum over the group (G = 2, 3, 4, 8, 12, 16, 24; the paper's models
+    use G = 2, its kernel benchmarks G = 8 and, in two rows, 16 and 32)."""
     check_full(2, Hq, T, d, L, 500 + T + L, depth_alloc=La, Hk=Hk)
 
 
