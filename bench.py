@@ -125,7 +125,7 @@ def run_paper_table2(args):
         inp = synth.make_inputs(1, Hq, Hk, T, 64, L, dtype="bf16", seed=5, device="cuda", with_dO=True)
         O = torch.empty_like(inp["Q"])
         LSE = torch.empty((1, Hq, T), dtype=torch.float32, device="cuda")
-        ws = torch.empty(4 * Hq * T + 256, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(8 * Hq * T + 256, dtype=torch.uint8, device="cuda")
         with_bwd = G <= 64
         out = {"row": no, "T": T, "G": G, "Hq": Hq, "Hk": Hk, "depth_count": L, "backward_included": with_bwd,
                "paper_a100_ms": {"fa2": p_fa, "moda": p_moda, "extra_pct": round(100 * (p_moda - p_fa) / p_moda, 2)}}
@@ -181,7 +181,7 @@ def run_backward(args, B, Hq, Hk, T, d, L, dtype):
 
     inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=4, device="cuda", with_dO=True)
     O, LSE = moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], depth_count=L)
-    ws = torch.empty(4 * B * Hq * T + 256, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(8 * B * Hq * T + 256, dtype=torch.uint8, device="cuda")
 
     def run():
         moda_attn_bwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], O, LSE, inp["dO"],

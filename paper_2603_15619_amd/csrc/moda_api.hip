@@ -182,7 +182,7 @@ moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, con
   p.Q = Q; p.Kseq = Kseq; p.Vseq = Vseq; p.Kdepth = Kdepth; p.Vdepth = Vdepth;
   p.O = O; p.LSE = LSE; p.dO = dO;
   p.dQ = dQ; p.dKseq = dKseq; p.dVseq = dVseq; p.dKdepth = dKdepth; p.dVdepth = dVdepth;
-  p.delta = static_cast<float*>(workspace);
+  p.rowstat = static_cast<float*>(workspace);
   p.B = s->B; p.Hq = s->Hq; p.Hk = s->Hk; p.T = s->T;
   p.depth_alloc = s->depth_alloc; p.depth_count = s->depth_count;
   p.causal = s->causal;

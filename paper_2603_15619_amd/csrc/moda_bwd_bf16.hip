@@ -30,10 +30,13 @@ namespace moda {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// ---------------------------------------------------------------- delta_t = <dO_t, O_t>
+// ---------------------------------------------------------------- per-row scalars
+// rowstat[row] = (LSE_row * log2(e), delta_row = <dO_row, O_row>), interleaved, for the other
+// kernels (they exponentiate with exp2; the pairs of a query tile are one contiguous block
+// that is copied to LDS without passing through registers).
 template <int D>
-__global__ __launch_bounds__(256) void moda_bwd_delta_kernel(const void* dO, const void* O, float* delta,
-                                                             long long rows) {
+__global__ __launch_bounds__(256) void moda_bwd_delta_kernel(const void* dO, const void* O, const float* LSE,
+                                                             float* rowstat, long long rows) {
   constexpr int LPR = D / 8;  // lanes per row, 8 channels each
   const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) / LPR;
   const int l = threadIdx.x % LPR;
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(256) void moda_bwd_delta_kernel(const void* dO, con
 #pragma unroll
   for (int k = 0; k < 4; ++k) s = dot2_bf16(a[k], b[k], s);
   s = group_sum<LPR>(s);
-  if (l == 0 && row < rows) delta[row] = s;
+  if (l == 0 && row < rows) *(f32x2*)(rowstat + 2 * row) = (f32x2){LSE[row] * kLog2e, s};
 }
 
 template <int D, int NW = 4>
@@ -53,7 +56,7 @@ struct BwdCfg {
   static constexpr int kXWave = 32 * kXRow;       // 32 rows per wave
   static constexpr int kXBytes = NW * kXWave;
   static constexpr int kStageBytes = 2 * Tile<D>::kBytes;  // two tiles per stage
-  static constexpr int kAux = 2 * 2 * 64 * 4;     // per stage: lse2[64], delta[64] (dkdv only)
+  static constexpr int kAux = 2 * 2 * 64 * 4;     // per stage: (lse2, delta) of 64 queries (dkdv only)
   static constexpr int kRing = 2 * kStageBytes;
   static constexpr int kLds = (kRing > kXBytes ? kRing : kXBytes) + kAux;
 };
@@ -112,17 +115,26 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   TileLoader<D> ld;
   ld.init(wave, lane);
+  FragAddr<D> fa;
+  fa.init(lane);
 
   auto issue = [&](int item, int stage) {
     const int bh = bh0 + item / span, qt = qt0 + item % span;
-    const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
-    const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
-    ld.issue(Qb, qt * 64, T, smem_addr + stage * C::kStageBytes);
-    ld.issue(dOb, qt * 64, T, smem_addr + stage * C::kStageBytes + Tl::kBytes);
-    if (tid < 64) {
-      const int r = min(qt * 64 + tid, T - 1);
-      aux[stage * 128 + tid] = p.LSE[(size_t)bh * T + r] * kLog2e;
-      aux[stage * 128 + 64 + tid] = p.delta[(size_t)bh * T + r];
+    const i32x4 q_buf = make_tile_buffer((const char*)p.Q + (size_t)bh * T * Tl::kRowBytes, (unsigned)T * Tl::kRowBytes);
+    const i32x4 do_buf = make_tile_buffer((const char*)p.dO + (size_t)bh * T * Tl::kRowBytes, (unsigned)T * Tl::kRowBytes);
+    ld.issue(q_buf, qt * 64, smem_addr + stage * C::kStageBytes);
+    ld.issue(do_buf, qt * 64, smem_addr + stage * C::kStageBytes + Tl::kBytes);
+    // (lse2, delta) of the tile's 64 queries: 512 contiguous bytes, copied like the tiles (no
+    // load whose result a wave would have to wait for while the tile copies are in flight:
+    // memory operations complete in order); waves 0 and 1 copy 256 bytes each
+    if (wave < 2) {
+      const i32x4 st_buf = make_tile_buffer(p.rowstat + (size_t)bh * T * 2, (unsigned)T * 8);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                   :
+                   : "s"(__builtin_amdgcn_readfirstlane((int)(smem_addr + (unsigned)(C::kLds - C::kAux) +
+                                                               stage * 512 + wave * 256))),
+                     "v"(lane * 4), "s"(st_buf), "s"(__builtin_amdgcn_readfirstlane(qt * 512 + wave * 256))
+                   : "memory");
     }
   };
 
@@ -136,10 +148,9 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 
     const int q0 = qt * 64;
     if (p.causal && q0 + 63 < kw0) continue;  // every query of the tile precedes this wave's keys
-    const unsigned char* qtile = smem + stage * C::kStageBytes;
-    const unsigned char* dotile = qtile + Tl::kBytes;
-    const float* lse_s = aux + stage * 128;
-    const float* del_s = lse_s + 64;
+    const unsigned qtile = smem_addr + stage * C::kStageBytes;
+    const unsigned dotile = qtile + Tl::kBytes;
+    const float* stat_s = aux + stage * 128;  // (lse2, delta) pairs of the tile's queries
 
     const int key = kw0 + l32;
     // one 32-query block at a time: S, dP (recomputed), P and dS for this lane's key and
@@ -151,8 +162,8 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
       for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
 #pragma unroll
       for (int st = 0; st < Tl::kDSteps; ++st) {
-        s = mfma_bf16(Tl::row_frag(qtile, qb, st, lane), kf[st], s);
-        dp = mfma_bf16(Tl::row_frag(dotile, qb, st, lane), vf[st], dp);
+        s = mfma_bf16(fa.row_frag(qtile, qb, st), kf[st], s);
+        dp = mfma_bf16(fa.row_frag(dotile, qb, st), vf[st], dp);
         // (fragment reads are not hoisted across this point: with all of a tile's reads
         //  issued up front the kernel runs out of registers and spills K / V fragments)
         if (st == Tl::kDSteps - 1) __builtin_amdgcn_sched_barrier(0);
@@ -165,14 +176,18 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 #pragma unroll
         for (int b2 = 0; b2 < 2; ++b2) {
           const int b4 = hf * 2 + b2;
-          const f32x4 l4 = *(const f32x4*)(lse_s + qb * 32 + b4 * 8 + hi * 4);
-          const f32x4 d4 = *(const f32x4*)(del_s + qb * 32 + b4 * 8 + hi * 4);
+          const float* st4 = stat_s + (qb * 32 + b4 * 8 + hi * 4) * 2;
+          const f32x4 ld01 = *(const f32x4*)st4, ld23 = *(const f32x4*)(st4 + 4);
+          const float l4[4] = {ld01[0], ld01[2], ld23[0], ld23[2]};
+          const float d4[4] = {ld01[1], ld01[3], ld23[1], ld23[3]};
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const int i = b4 * 4 + r;
             const int q = q0 + qb * 32 + b4 * 8 + hi * 4 + r;
             const bool vis = q < T && (!p.causal || key <= q);
-            const float pe = vis ? fast_exp2(s[i] * c2 - l4[r]) : 0.f;
+            // (a select on the argument, not on the result: the compiler turns the latter into a
+            //  branch around the exponential, one per element)
+            const float pe = fast_exp2(vis ? s[i] * c2 - l4[r] : -INFINITY);
             pv[b2 * 4 + r] = pe;
             dsv[b2 * 4 + r] = pe * (dp[i] - d4[r]);
           }
@@ -180,8 +195,8 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
         const bf16x8 pb = pack8(pv), dsb = pack8(dsv);
 #pragma unroll
         for (int db = 0; db < Tl::kDBlocks; ++db) {
-          dv[db] = mfma_bf16(Tl::tr_frag(dotile, qb * 2 + hf, db, lane), pb, dv[db]);
-          dk[db] = mfma_bf16(Tl::tr_frag(qtile, qb * 2 + hf, db, lane), dsb, dk[db]);
+          dv[db] = mfma_bf16(fa.tr_frag(dotile, qb * 2 + hf, db), pb, dv[db]);
+          dk[db] = mfma_bf16(fa.tr_frag(qtile, qb * 2 + hf, db), dsb, dk[db]);
 
         }
       }
@@ -254,8 +269,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const char* Kb = (const char*)p.Kseq + (size_t)bg * T * Tl::kRowBytes;
   const char* Vb = (const char*)p.Vseq + (size_t)bg * T * Tl::kRowBytes;
   const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
-  const float* LSEb = p.LSE + (size_t)bh * T;
-  const float* Db = p.delta + (size_t)bh * T;
+  const float* statb = p.rowstat + (size_t)bh * T * 2;  // (LSE * log2(e), delta) per row
 
   // resident Q and dO fragments of this wave's 32 queries (MFMA B operands)
   bf16x8 qf[Tl::kDSteps], dof[Tl::kDSteps];
@@ -266,8 +280,8 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     qf[st] = *(const bf16x8*)(Qb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
     dof[st] = *(const bf16x8*)(dOb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
   }
-  const float lse2 = LSEb[qrow] * kLog2e;
-  const float delta = Db[qrow];
+  const f32x2 stat = *(const f32x2*)(statb + 2 * qrow);
+  const float lse2 = stat[0], delta = stat[1];
 
   const float c2 = p.scale_log2;
   unsigned char* xw = smem + wave * C::kXWave;  // this wave's fp32 exchange buffer (overlaps the ring)
@@ -350,8 +364,9 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
       const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1; nothing of them is stored
       b.q = *(const u32x4*)(Qb + (size_t)tc * Tl::kRowBytes + l16 * 16);
       b.g = *(const u32x4*)(dOb + (size_t)tc * Tl::kRowBytes + l16 * 16);
-      b.l2 = LSEb[tc] * kLog2e;
-      b.dl = Db[tc];
+      const f32x2 st = *(const f32x2*)(statb + 2 * tc);
+      b.l2 = st[0];
+      b.dl = st[1];
       const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
       // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
 #pragma unroll
@@ -510,9 +525,13 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
   TileLoader<D, NW> ld;
   ld.init(wave, lane);
+  FragAddr<D> fa;
+  fa.init(lane);
+  const i32x4 k_buf = make_tile_buffer(Kb, (unsigned)T * Tl::kRowBytes);
+  const i32x4 v_buf = make_tile_buffer(Vb, (unsigned)T * Tl::kRowBytes);
   auto issue = [&](int kt, int stage) {
-    ld.issue(Kb, kt * 64, T, smem_addr + stage * C::kStageBytes);
-    ld.issue(Vb, kt * 64, T, smem_addr + stage * C::kStageBytes + Tl::kBytes);
+    ld.issue(k_buf, kt * 64, smem_addr + stage * C::kStageBytes);
+    ld.issue(v_buf, kt * 64, smem_addr + stage * C::kStageBytes + Tl::kBytes);
   };
 
   issue(0, 0);
@@ -522,8 +541,8 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     __syncthreads();
     if (kt + 1 < nt) issue(kt + 1, stage ^ 1);
     if (kt > wave_last) continue;
-    const unsigned char* ktile = smem + stage * C::kStageBytes;
-    const unsigned char* vtile = ktile + Tl::kBytes;
+    const unsigned ktile = smem_addr + stage * C::kStageBytes;
+    const unsigned vtile = ktile + Tl::kBytes;
 
     f32x16 s[2], dp[2];  // S^T, dP^T: [key block]; a lane holds 16 keys of its query
 #pragma unroll
@@ -532,8 +551,8 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
       for (int i = 0; i < 16; ++i) s[kb][i] = dp[kb][i] = 0.f;
 #pragma unroll
       for (int st = 0; st < Tl::kDSteps; ++st) {
-        s[kb] = mfma_bf16(Tl::row_frag(ktile, kb, st, lane), qf[st], s[kb]);
-        dp[kb] = mfma_bf16(Tl::row_frag(vtile, kb, st, lane), dof[st], dp[kb]);
+        s[kb] = mfma_bf16(fa.row_frag(ktile, kb, st), qf[st], s[kb]);
+        dp[kb] = mfma_bf16(fa.row_frag(vtile, kb, st), dof[st], dp[kb]);
       }
     }
     bf16x8 dsb[2][2];
@@ -544,7 +563,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int key = k0 + kb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
-        const float pe = key <= lim ? fast_exp2(s[kb][i] * c2 - lse2) : 0.f;
+        const float pe = fast_exp2(key <= lim ? s[kb][i] * c2 - lse2 : -INFINITY);
         dsv[i] = pe * (dp[kb][i] - delta);
       }
 #pragma unroll
@@ -560,7 +579,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int db = 0; db < Tl::kDBlocks; ++db)
-        dq[db] = mfma_bf16(Tl::tr_frag(ktile, ks, db, lane), dsb[ks >> 1][ks & 1], dq[db]);
+        dq[db] = mfma_bf16(fa.tr_frag(ktile, ks, db), dsb[ks >> 1][ks & 1], dq[db]);
   }
   __syncthreads();
 
@@ -624,8 +643,9 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p, in
     const int bh = bh0 + min(head0 + j, G - 1);  // heads past the group repeat the last one with weight zero
     q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
     g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
-    l2[j] = p.LSE[(size_t)bh * T + t] * kLog2e;
-    dl[j] = p.delta[(size_t)bh * T + t];
+    const f32x2 st = *(const f32x2*)(p.rowstat + ((size_t)bh * T + t) * 2);
+    l2[j] = st[0];
+    dl[j] = st[1];
 #pragma unroll
     for (int k = 0; k < 8; ++k) dq[j][k] = 0.f;
   }
@@ -711,7 +731,7 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p, in
 }
 
 // ---------------------------------------------------------------- launchers
-size_t bwd_bf16_workspace_bytes(const BwdParams& p) { return (size_t)p.B * p.Hq * p.T * sizeof(float); }
+size_t bwd_bf16_workspace_bytes(const BwdParams& p) { return (size_t)p.B * p.Hq * p.T * 2 * sizeof(float); }
 
 int bwd_bf16_max_group() { return 64; }
 
@@ -728,7 +748,8 @@ static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
   const long long g_depth = (kv_rows * (D / 8) + 255) / 256;
   if (g_delta > 0x7fffffffLL || g_dq > 0x7fffffffLL || g_depth > 0x7fffffffLL) return hipErrorInvalidValue;
   if (G > bwd_bf16_max_group()) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.delta, rows);
+  hipLaunchKernelGGL(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.LSE,
+                     p.rowstat, rows);
   if (G > 1 && p.depth_alloc > 0) {
     if (G <= 2)
       hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 2>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, 0);

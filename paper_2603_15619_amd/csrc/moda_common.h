@@ -50,7 +50,7 @@ struct BwdParams {
   void* dVseq;
   void* dKdepth;
   void* dVdepth;
-  float* delta;  // workspace: <dO_t, O_t> per row, [B, Hq, T]
+  float* rowstat;  // workspace: (LSE_t * log2(e), <dO_t, O_t>) per row, [B, Hq, T, 2]
   int B, Hq, Hk, T;
   int depth_alloc, depth_count;
   int causal;

@@ -49,75 +49,116 @@ struct Tile {
   }
   // byte offset of the 16-byte chunk c of row r
   __device__ static __forceinline__ int off(int r, int c) { return r * kRowBytes + ((c ^ swz(r)) << 4); }
-  // row fragment: rows rb*32 .. rb*32+31, channel step st
-  __device__ static __forceinline__ bf16x8 row_frag(const unsigned char* tile, int rb, int st, int lane) {
+};
+
+// x ^ c, evaluated where it is written.  The compiler would otherwise precompute one address
+// per fragment outside the loops and keep them all in registers; the kernels that use these
+// tiles have none to spare, the addresses end up in scratch memory, and every reload from
+// scratch waits for ALL earlier memory operations, the tile copies in flight included.
+__device__ __forceinline__ int xor_here(int x, int c) {
+  if (c == 0) return x;
+  int r;
+  asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "s"(c), "v"(x));
+  return r;
+}
+
+// Per-lane fragment addresses inside a tile: three registers and constants.  Channel step st
+// of a row fragment and channel block db of a transposed fragment only flip bits 5..7 of the
+// chunk field (an XOR, because the chunk index is permuted by an XOR); row blocks are
+// immediates.
+template <int D>
+struct FragAddr {
+  using Tl = Tile<D>;
+  int row;  // chunk `hi` of row l32 (st = 0, rb = 0)
+  int tr;   // first read of transposed fragment (ks = 0, db = 0)
+  int tr8;  // second read: the rows 8 further on
+  __device__ __forceinline__ void init(int lane) {
     const int l32 = lane & 31, hi = lane >> 5;
-    return *(const bf16x8*)(tile + off(rb * 32 + l32, st * 2 + hi));
+    row = Tl::off(l32, hi);
+    const int rr = hi * 4 + ((lane & 15) >> 2);
+    const int grp = (lane >> 4) & 1;
+    // this lane's 8 bytes: piece (lane & 3) of the two chunks of a 16-channel block; at d = 128
+    // the permutation keeps the two chunks adjacent, at d = 64 chunks are permuted one by one
+    if constexpr (D == 128) {
+      tr = Tl::off(rr, grp * 2) + (lane & 3) * 8;
+      tr8 = Tl::off(rr + 8, grp * 2) + (lane & 3) * 8;
+    } else {
+      const int ch = grp * 2 + ((lane & 3) >> 1);
+      tr = Tl::off(rr, ch) + (lane & 1) * 8;
+      tr8 = Tl::off(rr + 8, ch) + (lane & 1) * 8;
+    }
+  }
+  // row fragment of the tile at LDS byte address `tile`: rows rb*32 .. rb*32+31, channel step st
+  __device__ __forceinline__ bf16x8 row_frag(unsigned tile, int rb, int st) const {
+    const unsigned a = tile + rb * 32 * Tl::kRowBytes + (unsigned)xor_here(row, st << 5);
+    return *(const bf16x8 __attribute__((address_space(3)))*)(size_t)a;
   }
   // transposed fragment: rows ks*16 .. ks*16+15, channels db*32 .. db*32+31
-  __device__ static __forceinline__ bf16x8 tr_frag(const unsigned char* tile, int ks, int db, int lane) {
-    const int hi = lane >> 5;
-    const int rr = ks * 16 + hi * 4 + ((lane & 15) >> 2);
-    // this lane's 8 bytes: piece (lane & 3) of the two chunks of a 16-channel block.  At
-    // d = 128 the permutation keeps the two chunks adjacent and the rows r, r + 8 alike (one
-    // address computation serves both); at d = 64 chunks are permuted one by one.
-    const unsigned char *a0, *a1;
-    if constexpr (D == 128) {
-      const int ch = db * 4 + ((lane >> 4) & 1) * 2;
-      a0 = tile + off(rr, ch) + (lane & 3) * 8;
-      a1 = a0 + 8 * kRowBytes;
-    } else {
-      const int ch = db * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
-      a0 = tile + off(rr, ch) + (lane & 1) * 8;
-      a1 = tile + off(rr + 8, ch) + (lane & 1) * 8;
-    }
-    s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
-    s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a1);
+  __device__ __forceinline__ bf16x8 tr_frag(unsigned tile, int ks, int db) const {
+    const unsigned a0 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr, db << 6);
+    const unsigned a1 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
+    s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a0);
+    s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a1);
     s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v01);
   }
 };
 
 // 16 bytes per lane, global -> LDS without register staging: lane i's bytes land at
-// lds_addr + 16 i.  Completion is awaited with wait_copies() before the barrier that
-// publishes the tile.
-__device__ __forceinline__ void tile_copy16(const char* gbase, int voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+// lds_addr + 16 i.  The source is a raw buffer (base, size in bytes): lanes whose offset falls
+// outside it fetch nothing and write zeros, so rows past the end of the matrix need no
+// clamping (callers mask them).  Completion is awaited with wait_copies() before the barrier
+// that publishes the tile.
+__device__ __forceinline__ i32x4 make_tile_buffer(const void* base, unsigned bytes) {
+  const unsigned long long b = (unsigned long long)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(b & 0xffffffffu));
+  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((b >> 32) & 0xffffu));  // stride 0
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;  // 32-bit untyped data
+  return r;
+}
+__device__ __forceinline__ void tile_copy16(const i32x4& rsrc, int voff, int soff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
-               : "s"(lds_addr), "v"(voff), "s"(gbase)
+               : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rsrc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
                : "memory");
 }
 __device__ __forceinline__ void wait_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-// Copies rows [row0, row0+64) of a [n_rows, D] bf16 matrix into a tile; rows past
-// n_rows re-read the last row (callers mask them).  All NW waves of the workgroup take part.
+// Copies rows [row0, row0+64) of a [n_rows, D] bf16 matrix (behind `rsrc`) into a tile, 1 KB
+// pieces (1024 / row bytes rows each), piece q by copy instruction q % kInstPerWave of wave
+// q / kInstPerWave.  The chunk permutation is applied by choosing which global chunk a lane
+// fetches.  ONE per-lane register serves all pieces: the permutation of piece q differs from
+// piece 0's by a constant XOR that only depends on the parity of q (see swz), and everything
+// else is wave-uniform.  (With one offset register per piece, the compiler spilled them, and a
+// reload from scratch memory in front of every copy instruction waits for ALL earlier memory
+// operations, the previous copy included: the copies of a tile then ran one memory round trip
+// after the other.)
 template <int D, int NW = 4>
 struct TileLoader {
   static constexpr int kRowsPerInst = 64 / Tile<D>::kChunks;
   static constexpr int kInstPerWave = 64 / kRowsPerInst / NW;
   static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
-  int goff[kInstPerWave];
-  int row[kInstPerWave];
+  // byte XOR between the offsets of an odd and an even piece
+  static constexpr int kOddXor = (D == 128 ? 8 : 2) << 4;
+  int goff;
   int wave;
   __device__ __forceinline__ void init(int wave_, int lane) {
     wave = wave_;
-#pragma unroll
-    for (int i = 0; i < kInstPerWave; ++i) {
-      const int r = (wave * kInstPerWave + i) * kRowsPerInst + lane / Tile<D>::kChunks;
-      const int pc = lane % Tile<D>::kChunks;  // chunk position this lane fills
-      const int c = pc ^ Tile<D>::swz(r);
-      row[i] = r;
-      goff[i] = r * Tile<D>::kRowBytes + c * 16;
-    }
+    const int j = lane / Tile<D>::kChunks;   // row inside the piece
+    const int pc = lane % Tile<D>::kChunks;  // chunk position this lane fills
+    goff = j * Tile<D>::kRowBytes + ((pc ^ Tile<D>::swz(j)) << 4);
+    if (kInstPerWave == 1 && (wave & 1)) goff ^= kOddXor;  // a wave's only piece is odd
   }
-  __device__ __forceinline__ void issue(const char* gmat, int row0, int n_rows, unsigned lds_addr) const {
-    const char* gt = gmat + (size_t)row0 * Tile<D>::kRowBytes;
-    const int valid = n_rows - row0;
+  __device__ __forceinline__ void issue(const i32x4& rsrc, int row0, unsigned lds_addr) const {
 #pragma unroll
     for (int i = 0; i < kInstPerWave; ++i) {
-      const int r = min(row[i], valid - 1);
-      tile_copy16(gt, goff[i] + (r - row[i]) * Tile<D>::kRowBytes,
-                  lds_addr + (wave * kInstPerWave + i) * kRowsPerInst * Tile<D>::kRowBytes);
+      const int q = wave * kInstPerWave + i;
+      int voff = goff;
+      if (kInstPerWave > 1 && (i & 1)) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(voff) : "n"(kOddXor), "v"(goff));
+      tile_copy16(rsrc, voff, row0 * Tile<D>::kRowBytes + q * 1024, lds_addr + q * 1024);
     }
   }
 };
