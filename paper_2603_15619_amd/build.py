@@ -153,7 +153,7 @@ def check_named_acc_registers(src) -> None:
 # reload anything from scratch memory there: memory operations complete in order, so waiting
 # for a reload also waits for the copies (measured on the dK/dV kernel: 1.9 ms with 100 bytes
 # of scratch per lane, 1.55 ms with none).  (source file, substring of the mangled kernel name)
-NO_SCRATCH_KERNELS = (("moda_bwd_bf16.hip", "moda_bwd_dkdv_kernel"),)
+NO_SCRATCH_KERNELS = (("moda_bwd_bf16.hip", "moda_bwd_dkdv_kernel"), ("moda_bwd_bf16.hip", "moda_bwd_dq_kernel"))
 
 
 def check_no_scratch(src, name_part) -> None:

@@ -271,17 +271,8 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
   const float* statb = p.rowstat + (size_t)bh * T * 2;  // (LSE * log2(e), delta) per row
 
-  // resident Q and dO fragments of this wave's 32 queries (MFMA B operands)
-  bf16x8 qf[Tl::kDSteps], dof[Tl::kDSteps];
   const int qi = qw0 + l32;
   const int qrow = min(qi, T - 1);
-#pragma unroll
-  for (int st = 0; st < Tl::kDSteps; ++st) {
-    qf[st] = *(const bf16x8*)(Qb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
-    dof[st] = *(const bf16x8*)(dOb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
-  }
-  const f32x2 stat = *(const f32x2*)(statb + 2 * qrow);
-  const float lse2 = stat[0], delta = stat[1];
 
   const float c2 = p.scale_log2;
   unsigned char* xw = smem + wave * C::kXWave;  // this wave's fp32 exchange buffer (overlaps the ring)
@@ -517,6 +508,17 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
   }
+
+  // resident Q and dO fragments of this wave's 32 queries (MFMA B operands); loaded only now,
+  // so that they do not occupy registers during a depth phase that runs first
+  bf16x8 qf[Tl::kDSteps], dof[Tl::kDSteps];
+#pragma unroll
+  for (int st = 0; st < Tl::kDSteps; ++st) {
+    qf[st] = *(const bf16x8*)(Qb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
+    dof[st] = *(const bf16x8*)(dOb + (size_t)qrow * Tl::kRowBytes + st * 32 + hi * 16);
+  }
+  const f32x2 stat = *(const f32x2*)(statb + 2 * qrow);
+  const float lse2 = stat[0], delta = stat[1];
 
   const int n_keys = p.causal ? min(T, q0 + kQT) : T;
   const int nt = (n_keys + 63) / 64;
