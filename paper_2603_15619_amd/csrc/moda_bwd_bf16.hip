@@ -164,10 +164,17 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
       for (int st = 0; st < Tl::kDSteps; ++st) {
         s = mfma_bf16(fa.row_frag(qtile, qb, st), kf[st], s);
         dp = mfma_bf16(fa.row_frag(dotile, qb, st), vf[st], dp);
-        // (fragment reads are not hoisted across this point: with all of a tile's reads
-        //  issued up front the kernel runs out of registers and spills K / V fragments)
-        if (st == Tl::kDSteps - 1) __builtin_amdgcn_sched_barrier(0);
       }
+      // Order for the scheduler: LDS reads run one step (two fragments) ahead of the matrix
+      // instructions that consume them, no further (the kernel has no registers to spare).
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int st = 0; st < Tl::kDSteps - 2; ++st) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_barrier(0);
       // one 16-query half at a time: P and dS packed to bf16, then straight into the products
       // that contract over those 16 queries (keeps few temporaries alive)
 #pragma unroll
@@ -197,8 +204,8 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
         for (int db = 0; db < Tl::kDBlocks; ++db) {
           dv[db] = mfma_bf16(fa.tr_frag(dotile, qb * 2 + hf, db), pb, dv[db]);
           dk[db] = mfma_bf16(fa.tr_frag(qtile, qb * 2 + hf, db), dsb, dk[db]);
-
         }
+
       }
     }
   }
@@ -557,6 +564,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
         dp[kb] = mfma_bf16(fa.row_frag(vtile, kb, st), dof[st], dp[kb]);
       }
     }
+
     bf16x8 dsb[2][2];
     const int k0 = kt * 64;
 #pragma unroll
