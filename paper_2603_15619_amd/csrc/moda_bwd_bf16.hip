@@ -6,21 +6,23 @@
 //   p_c = exp(scale <q_t, k_c> - LSE_t),  delta_t = <dO_t, O_t>,
 //   dV_c += p_c dO_t,  e_c = p_c (<dO_t, v_c> - delta_t),
 //   dQ_t = scale sum_c e_c k_c,  dK_c += scale e_c q_t.
-// Three kernels, no atomics, every output element written exactly once:
-//   delta  : delta_t for every row (row-parallel, vector ALUs).
+// Three kernels (four with grouped queries), no atomics, every output element written
+// exactly once:
+//   delta  : (LSE_t log2(e), delta_t) for every row (row-parallel, vector ALUs).
 //   dkdv   : one workgroup per 128 sequence keys; Q / dO tiles stream through LDS;
 //            S = Q K^T and dP = dO V^T are recomputed per 32x32 block on the MFMA
 //            pipe, P and dS = P (dP - delta) are packed to bf16 straight out of the
-//            accumulators and contracted over the queries into dV^T, dK^T.
+//            accumulators and contracted over the queries into dV^T, dK^T.  The same
+//            workgroup also takes the depth slots of its 128 positions (row-local: dKdepth,
+//            dVdepth and the depth share of dQ, left in the dQ buffer), before or after its
+//            key-tile work: that part is bound by HBM, the rest by the matrix pipe.
 //   dq     : one workgroup per 128 queries; K / V tiles stream through LDS; S^T, dP^T
 //            are recomputed in the transposed orientation (a lane owns one query),
-//            dQ^T += K^T dS^T; then, in a row-major epilogue, the depth slots of the
-//            query's own position give dKdepth, dVdepth (row-local, written once)
-//            and their share of dQ.
+//            dQ^T += K^T dS^T on top of the depth share found in the dQ buffer.
 // Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 64): the
 // gradients of the shared keys and values sum over the group.  dkdv walks the query
-// tiles of all G heads; the depth-slot gradients move from the dq kernel's epilogue to a
-// kernel of their own (depth_gqa) that holds the G heads of a position side by side.
+// tiles of all G heads; the depth-slot gradients are computed by a kernel of their own
+// (depth_gqa) that holds the G heads of a position side by side.
 #include <type_traits>
 
 #include "moda_launch.h"
@@ -66,6 +68,189 @@ __device__ __forceinline__ bf16x8 pack8(const float (&x)[8]) {
   return __builtin_bit_cast(bf16x8, t);
 }
 
+// ---------------------------------------------------------------- depth-slot gradients (G = 1)
+// The depth slots of 32 consecutive positions (row0 ...) of one head, handled by one wave in a
+// row-major mapping (d/8 lanes x 8 channels per row, 64 / (d/8) rows per wave step): dKdepth,
+// dVdepth (row-local, written once) and the depth share of dQ, which is left in the dQ buffer
+// (not yet multiplied by the softmax scale, rounded to bf16) for the dQ kernel to start from.
+// Work items (row step, chunk of kChunk slots) are walked with the loads of the next two
+// items in flight (the phase is bound by memory latency).  Uses no LDS.
+template <int D>
+__device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int row0, int lane) {
+  using Tl = Tile<D>;
+  constexpr int LPR = Tl::kChunks, RPS = 64 / LPR, NIT = 32 / RPS;
+  constexpr int kChunk = 5;
+  const int T = p.T, L = p.depth_count, La = p.depth_alloc;
+  const int bg = bh, qw0 = row0;
+  const float c2 = p.scale_log2;
+  const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
+  const char* dOb = (const char*)p.dO + (size_t)bh * T * Tl::kRowBytes;
+  const float* statb = p.rowstat + (size_t)bh * T * 2;
+  const int rg = lane / LPR, l16 = lane % LPR;
+  const size_t drow = (size_t)La * Tl::kRowBytes;
+  const size_t slab = (size_t)T * drow;
+  // (this phase only runs when every key/value head serves one query head: bg == bh)
+  const char* Kdb = (const char*)p.Kdepth + (size_t)bg * slab;
+  const char* Vdb = (const char*)p.Vdepth + (size_t)bg * slab;
+  char* dKdb = (char*)p.dKdepth + (size_t)bg * slab;
+  char* dVdb = (char*)p.dVdepth + (size_t)bg * slab;
+  char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
+  // raw buffers with 32-bit offsets
+  const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Kdb, 0, (int)(unsigned)slab, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Vdb, 0, (int)(unsigned)slab, 0x00020000);
+  const __amdgpu_buffer_rsrc_t dkd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dKdb, 0, (int)(unsigned)slab, 0x00020000);
+  const __amdgpu_buffer_rsrc_t dvd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dVdb, 0, (int)(unsigned)slab, 0x00020000);
+  const int nch = (L + kChunk - 1) / kChunk;
+
+  struct Item {
+    u32x4 q, g;   // the row's Q and dO channels of this lane
+    float l2, dl;  // LSE * log2(e), delta
+    u32x4 k[kChunk], v[kChunk];
+  };
+  float acc[8];
+  auto begin_row = [&]() {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+  };
+  auto end_row = [&](int row) {
+    const int t = qw0 + row;
+    if (t < T) {
+      u32x4 ov = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
+                  pack_bf16(acc[6], acc[7])};
+      *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
+    }
+  };
+  if (L == 0) {  // no attended slots: a zero share of dQ, zero gradients for allocated slots
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPS + rg, t = qw0 + row;
+      begin_row();
+      end_row(row);
+      if (t < T) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = 0; i < La; ++i) {
+          *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+        }
+      }
+    }
+    return;
+  }
+  auto issue = [&](int it, int c, Item& b) {
+    const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1; nothing of them is stored
+    b.q = *(const u32x4*)(Qb + (size_t)tc * Tl::kRowBytes + l16 * 16);
+    b.g = *(const u32x4*)(dOb + (size_t)tc * Tl::kRowBytes + l16 * 16);
+    const f32x2 st = *(const f32x2*)(statb + 2 * tc);
+    b.l2 = st[0];
+    b.dl = st[1];
+    const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+    // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      b.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      b.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
+  };
+  auto fold = [&](int it, int c, const Item& b) {
+    const int t = qw0 + it * RPS + rg;
+    const bool live = t < T;  // rows past the end compute on row T-1 and store nothing
+    const int voff = (int)((unsigned)min(t, T - 1) * (unsigned)drow + (unsigned)l16 * 16u);
+    const int soff = c * kChunk * Tl::kRowBytes;
+    float qx[8], gx[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      qx[2 * k] = bf16_lo(b.q[k]);
+      qx[2 * k + 1] = bf16_hi(b.q[k]);
+      gx[2 * k] = bf16_lo(b.g[k]);
+      gx[2 * k + 1] = bf16_hi(b.g[k]);
+    }
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      float sdot = 0.f, gdot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        sdot = dot2_bf16(b.q[k], b.k[i][k], sdot);
+        gdot = dot2_bf16(b.g[k], b.v[i][k], gdot);
+      }
+      sdot = group_sum<LPR>(sdot);
+      gdot = group_sum<LPR>(gdot);
+      const int slot = c * kChunk + i;
+      if (slot >= L) {  // uniform
+        // slots past depth_count may hold anything (NaN included) and take no part; those
+        // that are allocated get zero gradients
+        if (slot < La && live) {
+          const u32x4 z = {0u, 0u, 0u, 0u};
+          __builtin_amdgcn_raw_buffer_store_b128(z, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
+          __builtin_amdgcn_raw_buffer_store_b128(z, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
+        }
+      } else {
+        const float pe = fast_exp2(sdot * c2 - b.l2);
+        const float e = pe * (gdot - b.dl);
+        const float es = e * p.scale;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc[2 * k] += e * bf16_lo(b.k[i][k]);
+          acc[2 * k + 1] += e * bf16_hi(b.k[i][k]);
+        }
+        const u32x4 o1 = {pack_bf16(pe * gx[0], pe * gx[1]), pack_bf16(pe * gx[2], pe * gx[3]),
+                          pack_bf16(pe * gx[4], pe * gx[5]), pack_bf16(pe * gx[6], pe * gx[7])};
+        const u32x4 o2 = {pack_bf16(es * qx[0], es * qx[1]), pack_bf16(es * qx[2], es * qx[3]),
+                          pack_bf16(es * qx[4], es * qx[5]), pack_bf16(es * qx[6], es * qx[7])};
+        if (live) {
+          __builtin_amdgcn_raw_buffer_store_b128(o1, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
+          __builtin_amdgcn_raw_buffer_store_b128(o2, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
+        }
+      }
+    }
+  };
+  int it = 0, c = 0, iti = 0, ci = 0;
+  auto advance = [&](int& i_, int& c_) {
+    if (++c_ == nch) {
+      c_ = 0;
+      ++i_;
+    }
+  };
+  // (past the end the issue cursor stays on the last item: its loads are repeated and ignored)
+  auto issue_next = [&](Item& b) {
+    issue(iti, ci, b);
+    int i2 = iti, c2n = ci;
+    advance(i2, c2n);
+    if (i2 < NIT) {
+      iti = i2;
+      ci = c2n;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto one = [&](const Item& cur, Item& refill) -> bool {
+    issue_next(refill);
+    const int row = it * RPS + rg;
+    if (c == 0) begin_row();
+    fold(it, c, cur);
+    if (c == nch - 1) {
+      end_row(row);
+      // allocated slots beyond the last chunk (depth_alloc > depth_count rounded up to a chunk)
+      const int t = qw0 + row;
+      if (t < T) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = nch * kChunk; i < La; ++i) {
+          *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+        }
+      }
+    }
+    advance(it, c);
+    return it < NIT;
+  };
+  Item bufA, bufB, bufC;
+  issue_next(bufA);
+  issue_next(bufB);
+  while (true) {
+    if (!one(bufA, bufC)) break;
+    if (!one(bufB, bufA)) break;
+    if (!one(bufC, bufB)) break;
+  }
+}
+
 // ---------------------------------------------------------------- dK, dV
 // Workgroup = 128 keys (4 waves x 32 keys).  Accumulators hold dK^T, dV^T
 // ([channel][key]: a lane owns one key and 64 of its channels).
@@ -90,6 +275,16 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 
   const char* Kb = (const char*)p.Kseq + (size_t)bg * T * Tl::kRowBytes;
   const char* Vb = (const char*)p.Vseq + (size_t)bg * T * Tl::kRowBytes;
+
+  // ---- Depth-slot gradients (one query head per key/value head; grouped queries have a kernel
+  // of their own): row-local, bound by HBM (every depth slot read once, every gradient written
+  // once), and independent of everything else this kernel does, which is bound by the matrix
+  // pipe and leaves HBM idle.  Each workgroup takes the 128 positions of its key tile, before
+  // its key-tile work (every other workgroup) or after it, so that at any time some compute
+  // units stream while others compute.
+  const bool own_depth = G == 1 && p.depth_alloc > 0;
+  const bool depth_first = ((blockIdx.x >> 3) & 1) != 0;
+  if (own_depth && depth_first) depth_grad_rows<D>(p, bg, kw0, lane);
 
   // resident K and V fragments of this wave's 32 keys (MFMA B operands: N = key, K = channels)
   bf16x8 kf[Tl::kDSteps], vf[Tl::kDSteps];
@@ -245,9 +440,10 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
+  if (own_depth && !depth_first) depth_grad_rows<D>(p, bg, kw0, lane);
 }
 
-// ---------------------------------------------------------------- dQ, dKdepth, dVdepth
+// ---------------------------------------------------------------- dQ
 // Workgroup = NW waves x 32 queries.  Accumulators hold dQ^T ([channel][query]: a lane owns
 // one query).  Launched with NW = 4 (two workgroups per compute unit); NW = 8 (one workgroup
 // per unit, a K/V tile serving twice as many queries) measured 6 % slower at B=8 H=16 T=4096.
@@ -286,207 +482,11 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   constexpr int LPR = Tl::kChunks, RPS = 64 / LPR, NIT = 32 / RPS;
   const int L = p.depth_count, La = p.depth_alloc;
 
-  // ---- Depth slots of the tile's own positions, row-major mapping (d/8 lanes x 8 channels per
-  // query row, 64 / (d/8) rows per wave step): dKdepth, dVdepth (row-local, written once) and
-  // the depth share of dQ.  MODE 0 (after the key loop): a row starts from the exchange
-  // buffer (the key loop's dQ), adds its depth share and is stored.  MODE 1 (before the key
-  // loop): a row starts from zero and leaves its depth share in the exchange buffer, from
-  // where the key loop picks it up.  Work items (row step, chunk of kChunk slots) are walked
-  // with the loads of the next two items in flight (the phase is bound by memory latency).
-  constexpr int kChunk = 5;
-  auto depth_grad = [&](auto MODE_T) {
-    constexpr int MODE = decltype(MODE_T)::value;
-    const int rg = lane / LPR, l16 = lane % LPR;
-    const size_t drow = (size_t)La * Tl::kRowBytes;
-    const size_t slab = (size_t)T * drow;
-    // (this phase only runs when every key/value head serves one query head: bg == bh)
-    const char* Kdb = (const char*)p.Kdepth + (size_t)bg * slab;
-    const char* Vdb = (const char*)p.Vdepth + (size_t)bg * slab;
-    char* dKdb = (char*)p.dKdepth + (size_t)bg * slab;
-    char* dVdb = (char*)p.dVdepth + (size_t)bg * slab;
-    char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
-    // raw buffers with 32-bit offsets
-    const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Kdb, 0, (int)(unsigned)slab, 0x00020000);
-    const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Vdb, 0, (int)(unsigned)slab, 0x00020000);
-    const __amdgpu_buffer_rsrc_t dkd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dKdb, 0, (int)(unsigned)slab, 0x00020000);
-    const __amdgpu_buffer_rsrc_t dvd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dVdb, 0, (int)(unsigned)slab, 0x00020000);
-    const int nch = (L + kChunk - 1) / kChunk;
-
-    struct Item {
-      u32x4 q, g;   // the row's Q and dO channels of this lane
-      float l2, dl;  // LSE * log2(e), delta
-      u32x4 k[kChunk], v[kChunk];
-    };
-    float acc[8];
-    auto begin_row = [&](int row) {
-      if constexpr (MODE == 1) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-      } else {
-        const f32x4 a0 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32);
-        const f32x4 a1 = *(const f32x4*)(xw + row * C::kXRow + l16 * 32 + 16);
-        acc[0] = a0[0]; acc[1] = a0[1]; acc[2] = a0[2]; acc[3] = a0[3];
-        acc[4] = a1[0]; acc[5] = a1[1]; acc[6] = a1[2]; acc[7] = a1[3];
-      }
-    };
-    auto end_row = [&](int row) {
-      if constexpr (MODE == 1) {
-        *(f32x4*)(xw + row * C::kXRow + l16 * 32) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
-        *(f32x4*)(xw + row * C::kXRow + l16 * 32 + 16) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
-      } else {
-        const int t = qw0 + row;
-        if (t < T) {
-          const float f = p.scale;
-          u32x4 ov = {pack_bf16(acc[0] * f, acc[1] * f), pack_bf16(acc[2] * f, acc[3] * f),
-                      pack_bf16(acc[4] * f, acc[5] * f), pack_bf16(acc[6] * f, acc[7] * f)};
-          *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
-        }
-      }
-    };
-    if (L == 0) {  // (MODE 0 only) no attended slots: dQ as it is, zero gradients for allocated slots
-      for (int it = 0; it < NIT; ++it) {
-        const int row = it * RPS + rg, t = qw0 + row;
-        begin_row(row);
-        end_row(row);
-        if (t < T) {
-          const u32x4 z = {0u, 0u, 0u, 0u};
-          for (int i = 0; i < La; ++i) {
-            *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-            *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-          }
-        }
-      }
-      return;
-    }
-    auto issue = [&](int it, int c, Item& b) {
-      const int tc = min(qw0 + it * RPS + rg, T - 1);  // rows past the end use row T-1; nothing of them is stored
-      b.q = *(const u32x4*)(Qb + (size_t)tc * Tl::kRowBytes + l16 * 16);
-      b.g = *(const u32x4*)(dOb + (size_t)tc * Tl::kRowBytes + l16 * 16);
-      const f32x2 st = *(const f32x2*)(statb + 2 * tc);
-      b.l2 = st[0];
-      b.dl = st[1];
-      const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
-      // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
-#pragma unroll
-      for (int i = 0; i < kChunk; ++i)
-        b.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
-#pragma unroll
-      for (int i = 0; i < kChunk; ++i)
-        b.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd_buf, voff, min(c * kChunk + i, L - 1) * Tl::kRowBytes, 2);
-    };
-    auto fold = [&](int it, int c, const Item& b) {
-      const int t = qw0 + it * RPS + rg;
-      const bool live = t < T;  // rows past the end compute on row T-1 and store nothing
-      const int voff = (int)((unsigned)min(t, T - 1) * (unsigned)drow + (unsigned)l16 * 16u);
-      const int soff = c * kChunk * Tl::kRowBytes;
-      float qx[8], gx[8];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        qx[2 * k] = bf16_lo(b.q[k]);
-        qx[2 * k + 1] = bf16_hi(b.q[k]);
-        gx[2 * k] = bf16_lo(b.g[k]);
-        gx[2 * k + 1] = bf16_hi(b.g[k]);
-      }
-#pragma unroll
-      for (int i = 0; i < kChunk; ++i) {
-        float sdot = 0.f, gdot = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          sdot = dot2_bf16(b.q[k], b.k[i][k], sdot);
-          gdot = dot2_bf16(b.g[k], b.v[i][k], gdot);
-        }
-        sdot = group_sum<LPR>(sdot);
-        gdot = group_sum<LPR>(gdot);
-        const int slot = c * kChunk + i;
-        if (slot >= L) {  // uniform
-          // slots past depth_count may hold anything (NaN included) and take no part; those
-          // that are allocated get zero gradients
-          if (slot < La && live) {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            __builtin_amdgcn_raw_buffer_store_b128(z, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
-            __builtin_amdgcn_raw_buffer_store_b128(z, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
-          }
-        } else {
-          const float pe = fast_exp2(sdot * c2 - b.l2);
-          const float e = pe * (gdot - b.dl);
-          const float es = e * p.scale;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            acc[2 * k] += e * bf16_lo(b.k[i][k]);
-            acc[2 * k + 1] += e * bf16_hi(b.k[i][k]);
-          }
-          const u32x4 o1 = {pack_bf16(pe * gx[0], pe * gx[1]), pack_bf16(pe * gx[2], pe * gx[3]),
-                            pack_bf16(pe * gx[4], pe * gx[5]), pack_bf16(pe * gx[6], pe * gx[7])};
-          const u32x4 o2 = {pack_bf16(es * qx[0], es * qx[1]), pack_bf16(es * qx[2], es * qx[3]),
-                            pack_bf16(es * qx[4], es * qx[5]), pack_bf16(es * qx[6], es * qx[7])};
-          if (live) {
-            __builtin_amdgcn_raw_buffer_store_b128(o1, dvd_buf, voff + i * Tl::kRowBytes, soff, 2);
-            __builtin_amdgcn_raw_buffer_store_b128(o2, dkd_buf, voff + i * Tl::kRowBytes, soff, 2);
-          }
-        }
-      }
-    };
-    int it = 0, c = 0, iti = 0, ci = 0;
-    auto advance = [&](int& i_, int& c_) {
-      if (++c_ == nch) {
-        c_ = 0;
-        ++i_;
-      }
-    };
-    // (past the end the issue cursor stays on the last item: its loads are repeated and ignored)
-    auto issue_next = [&](Item& b) {
-      issue(iti, ci, b);
-      int i2 = iti, c2n = ci;
-      advance(i2, c2n);
-      if (i2 < NIT) {
-        iti = i2;
-        ci = c2n;
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    auto one = [&](const Item& cur, Item& refill) -> bool {
-      issue_next(refill);
-      const int row = it * RPS + rg;
-      if (c == 0) begin_row(row);
-      fold(it, c, cur);
-      if (c == nch - 1) {
-        end_row(row);
-        // allocated slots beyond the last chunk (depth_alloc > depth_count rounded up to a chunk)
-        const int t = qw0 + row;
-        if (t < T) {
-          const u32x4 z = {0u, 0u, 0u, 0u};
-          for (int i = nch * kChunk; i < La; ++i) {
-            *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-            *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-          }
-        }
-      }
-      advance(it, c);
-      return it < NIT;
-    };
-    Item bufA, bufB, bufC;
-    issue_next(bufA);
-    issue_next(bufB);
-    while (true) {
-      if (!one(bufA, bufC)) break;
-      if (!one(bufB, bufA)) break;
-      if (!one(bufC, bufB)) break;
-    }
-  };
-  constexpr std::integral_constant<int, 0> kDepthLast{};
-  constexpr std::integral_constant<int, 1> kDepthFirst{};
-
-  // Every other workgroup takes its depth slots before the key loop, so that the compute
-  // units do not all stream from / to HBM at the same time and all compute at the same time
-  // (same reasoning as in the forward kernel; ids are dealt round-robin to the 8 dies).
-  // With grouped queries (G > 1) the depth-slot gradients sum over the group's query heads:
-  // moda_bwd_depth_gqa_kernel has computed them before this kernel and has left the depth
-  // share of dQ (not yet multiplied by the softmax scale, rounded to bf16) in the dQ buffer.
-  const bool external = G > 1;
-  const bool depth_first = !external && L > 0 && ((blockIdx.x >> 3) & 1) != 0;
-
+  // The depth-slot gradients and the depth share of dQ were computed before this kernel (by
+  // the dK/dV kernel, or by moda_bwd_depth_gqa_kernel with grouped queries); the share is in
+  // the dQ buffer, not yet multiplied by the softmax scale, rounded to bf16.
   f32x16 dq[Tl::kDBlocks];
-  if (external && La > 0) {
+  if (La > 0) {
     const char* src = (const char*)p.dQ + ((size_t)bh * T + qrow) * Tl::kRowBytes;
 #pragma unroll
     for (int db = 0; db < Tl::kDBlocks; ++db)
@@ -496,19 +496,6 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
         dq[db][4 * bq] = bf16_lo(v[0]); dq[db][4 * bq + 1] = bf16_hi(v[0]);
         dq[db][4 * bq + 2] = bf16_lo(v[1]); dq[db][4 * bq + 3] = bf16_hi(v[1]);
       }
-  } else if (depth_first) {
-    depth_grad(kDepthFirst);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-    for (int db = 0; db < Tl::kDBlocks; ++db)
-#pragma unroll
-      for (int bq = 0; bq < 4; ++bq) {
-        const f32x4 v = *(const f32x4*)(xw + l32 * C::kXRow + (db * 32 + bq * 8 + hi * 4) * 4);
-        dq[db][4 * bq] = v[0]; dq[db][4 * bq + 1] = v[1]; dq[db][4 * bq + 2] = v[2]; dq[db][4 * bq + 3] = v[3];
-      }
-    __syncthreads();  // every wave has its state: the buffer becomes the K/V ring
   } else {
 #pragma unroll
     for (int db = 0; db < Tl::kDBlocks; ++db)
@@ -516,8 +503,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
       for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
   }
 
-  // resident Q and dO fragments of this wave's 32 queries (MFMA B operands); loaded only now,
-  // so that they do not occupy registers during a depth phase that runs first
+  // resident Q and dO fragments of this wave's 32 queries (MFMA B operands)
   bf16x8 qf[Tl::kDSteps], dof[Tl::kDSteps];
 #pragma unroll
   for (int st = 0; st < Tl::kDSteps; ++st) {
@@ -604,9 +590,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  if (!depth_first && !external) {
-    depth_grad(kDepthLast);
-  } else {
+  {
     const int rg = lane / LPR, l16 = lane % LPR;
     char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
     for (int it = 0; it < NIT; ++it) {
