@@ -96,7 +96,9 @@ struct FragAddr {
   // transposed fragment: rows ks*16 .. ks*16+15, channels db*32 .. db*32+31
   __device__ __forceinline__ bf16x8 tr_frag(unsigned tile, int ks, int db) const {
     const unsigned a0 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr, db << 6);
-    const unsigned a1 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
+    // (at d = 128 the rows r and r + 8 are permuted alike: the second read is 8 rows further on)
+    const unsigned a1 = D == 128 ? a0 + 8 * Tl::kRowBytes
+                                 : tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
     s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a0);
     s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a1);
     s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
