@@ -9,13 +9,10 @@
 //   - a transposing read takes, per cycle, one 64-byte segment (4 chunks) of 4 consecutive
 //     rows: swz must send those rows to different 64-byte bank groups, i.e. differ in its
 //     bit 2 (and bit 3 at d = 128) among them.
-//   d = 64  ( 8 chunks, two rows = all banks): swz(r) = (((r >> 1) & 1) << 2) | ((r >> 2) & 3)
-//           meets both (measured: bank-conflict cycles 50-66 % -> 0, kernels 3-13 % faster).
-//   d = 128 (16 chunks, a row = all banks): ((r & 3) << 2) | ((r >> 2) & 3) meets both as well,
-//           but the rows r and r + 8 of a transposed fragment then differ in their permutation,
-//           which costs the dK/dV kernel four more address registers than it has (measured:
-//           conflicts 43 % -> 0, yet 1.78 -> 2.03 ms because of spills).  It keeps
-//           swz(r) = (r & 7) << 1, a 2-way conflict on both patterns.
+//   d = 128 (16 chunks, a row = all banks):      swz(r) = ((r & 3) << 2) | ((r >> 2) & 3);
+//   d = 64  ( 8 chunks, two rows = all banks):   swz(r) = (((r >> 1) & 1) << 2) | ((r >> 2) & 3).
+// Both meet both conditions (measured: bank-conflict cycles 43-66 % of the LDS cycles with the
+// pair permutation used before, 0 with these).
 // The access patterns:
 //   row fragment  (MFMA A operand, M = rows, K = channels): lane l reads 16 bytes of
 //                 row (l % 32), channels 16*st + 8*(l/32) .. +7;
@@ -45,7 +42,7 @@ struct Tile {
   static constexpr int kDBlocks = D / 32;
 
   __device__ static __forceinline__ int swz(int r) {
-    return D == 128 ? ((r & 7) << 1) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+    return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
   }
   // byte offset of the 16-byte chunk c of row r
   __device__ static __forceinline__ int off(int r, int c) { return r * kRowBytes + ((c ^ swz(r)) << 4); }
@@ -77,16 +74,11 @@ struct FragAddr {
     row = Tl::off(l32, hi);
     const int rr = hi * 4 + ((lane & 15) >> 2);
     const int grp = (lane >> 4) & 1;
-    // this lane's 8 bytes: piece (lane & 3) of the two chunks of a 16-channel block; at d = 128
-    // the permutation keeps the two chunks adjacent, at d = 64 chunks are permuted one by one
-    if constexpr (D == 128) {
-      tr = Tl::off(rr, grp * 2) + (lane & 3) * 8;
-      tr8 = Tl::off(rr + 8, grp * 2) + (lane & 3) * 8;
-    } else {
-      const int ch = grp * 2 + ((lane & 3) >> 1);
-      tr = Tl::off(rr, ch) + (lane & 1) * 8;
-      tr8 = Tl::off(rr + 8, ch) + (lane & 1) * 8;
-    }
+    // this lane's 8 bytes: piece (lane & 3) of the two chunks of a 16-channel block (chunks are
+    // permuted one by one, so the two need not be adjacent)
+    const int ch = grp * 2 + ((lane & 3) >> 1);
+    tr = Tl::off(rr, ch) + (lane & 1) * 8;
+    tr8 = Tl::off(rr + 8, ch) + (lane & 1) * 8;
   }
   // row fragment of the tile at LDS byte address `tile`: rows rb*32 .. rb*32+31, channel step st
   __device__ __forceinline__ bf16x8 row_frag(unsigned tile, int rb, int st) const {
@@ -96,9 +88,7 @@ struct FragAddr {
   // transposed fragment: rows ks*16 .. ks*16+15, channels db*32 .. db*32+31
   __device__ __forceinline__ bf16x8 tr_frag(unsigned tile, int ks, int db) const {
     const unsigned a0 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr, db << 6);
-    // (at d = 128 the rows r and r + 8 are permuted alike: the second read is 8 rows further on)
-    const unsigned a1 = D == 128 ? a0 + 8 * Tl::kRowBytes
-                                 : tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
+    const unsigned a1 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
     s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a0);
     s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a1);
     s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -143,8 +133,11 @@ struct TileLoader {
   static constexpr int kRowsPerInst = 64 / Tile<D>::kChunks;
   static constexpr int kInstPerWave = 64 / kRowsPerInst / NW;
   static_assert(kInstPerWave >= 1, "every wave copies part of every tile");
-  // byte XOR between the offsets of an odd and an even piece
-  static constexpr int kOddXor = (D == 128 ? 8 : 2) << 4;
+  // byte XOR between the offsets of piece q and piece 0: swz of the piece's first row
+  // (d = 128: 4 rows per piece, swz(4q) = q & 3; d = 64: 8 rows per piece, swz(8q) = (q & 1) << 1)
+  __device__ __host__ static constexpr int piece_xor(int q) { return (D == 128 ? (q & 3) : ((q & 1) << 1)) << 4; }
+  static_assert(kInstPerWave == 1 || kInstPerWave == 2 || kInstPerWave == 4,
+                "piece_xor(wave * kInstPerWave + i) = piece_xor(wave * kInstPerWave) ^ piece_xor(i)");
   int goff;
   int wave;
   __device__ __forceinline__ void init(int wave_, int lane) {
@@ -152,14 +145,13 @@ struct TileLoader {
     const int j = lane / Tile<D>::kChunks;   // row inside the piece
     const int pc = lane % Tile<D>::kChunks;  // chunk position this lane fills
     goff = j * Tile<D>::kRowBytes + ((pc ^ Tile<D>::swz(j)) << 4);
-    if (kInstPerWave == 1 && (wave & 1)) goff ^= kOddXor;  // a wave's only piece is odd
+    goff ^= piece_xor(wave * kInstPerWave);  // the wave's first piece; piece i of the wave: ^ piece_xor(i)
   }
   __device__ __forceinline__ void issue(const i32x4& rsrc, int row0, unsigned lds_addr) const {
 #pragma unroll
     for (int i = 0; i < kInstPerWave; ++i) {
       const int q = wave * kInstPerWave + i;
-      int voff = goff;
-      if (kInstPerWave > 1 && (i & 1)) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(voff) : "n"(kOddXor), "v"(goff));
+      const int voff = xor_here(goff, piece_xor(i));
       tile_copy16(rsrc, voff, row0 * Tile<D>::kRowBytes + q * 1024, lds_addr + q * 1024);
     }
   }
