@@ -258,7 +258,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   using Tl = Tile<D>;
   using C = BwdCfg<D>;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[C::kLds];
   float* aux = (float*)(smem + C::kLds - C::kAux);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -343,8 +343,9 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 
     const int q0 = qt * 64;
     if (p.causal && q0 + 63 < kw0) continue;  // every query of the tile precedes this wave's keys
+    // per-lane fragment bases inside this stage (Q tile; the dO tile sits Tl::kBytes after it)
     const unsigned qtile = smem_addr + stage * C::kStageBytes;
-    const unsigned dotile = qtile + Tl::kBytes;
+    const unsigned b_row = fa.row + qtile, b_tr = fa.tr + qtile, b_tr8 = fa.tr8 + qtile;
     const float* stat_s = aux + stage * 128;  // (lse2, delta) pairs of the tile's queries
 
     const int key = kw0 + l32;
@@ -357,8 +358,9 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
       for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
 #pragma unroll
       for (int st = 0; st < Tl::kDSteps; ++st) {
-        s = mfma_bf16(fa.row_frag(qtile, qb, st), kf[st], s);
-        dp = mfma_bf16(fa.row_frag(dotile, qb, st), vf[st], dp);
+        const unsigned x = (unsigned)xor_here((int)b_row, st << 5);
+        s = mfma_bf16(fa.row_frag(x, qb, 0), kf[st], s);
+        dp = mfma_bf16(fa.row_frag(x, qb, Tl::kBytes), vf[st], dp);
       }
       // Order for the scheduler: LDS reads run one step (two fragments) ahead of the matrix
       // instructions that consume them, no further (the kernel has no registers to spare).
@@ -397,8 +399,9 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
         const bf16x8 pb = pack8(pv), dsb = pack8(dsv);
 #pragma unroll
         for (int db = 0; db < Tl::kDBlocks; ++db) {
-          dv[db] = mfma_bf16(fa.tr_frag(dotile, qb * 2 + hf, db), pb, dv[db]);
-          dk[db] = mfma_bf16(fa.tr_frag(qtile, qb * 2 + hf, db), dsb, dk[db]);
+          const unsigned x0 = (unsigned)xor_here((int)b_tr, db << 6), x8 = (unsigned)xor_here((int)b_tr8, db << 6);
+          dv[db] = mfma_bf16(fa.tr_frag(x0, x8, qb * 2 + hf, Tl::kBytes), pb, dv[db]);
+          dk[db] = mfma_bf16(fa.tr_frag(x0, x8, qb * 2 + hf, 0), dsb, dk[db]);
         }
 
       }
@@ -452,7 +455,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   using Tl = Tile<D>;
   using C = BwdCfg<D, NW>;
   constexpr int kQT = NW * 32;  // queries per workgroup
-  __shared__ __attribute__((aligned(16))) unsigned char smem[C::kLds];
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[C::kLds];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -536,8 +539,9 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     __syncthreads();
     if (kt + 1 < nt) issue(kt + 1, stage ^ 1);
     if (kt > wave_last) continue;
+    // per-lane fragment bases inside this stage (K tile; the V tile sits Tl::kBytes after it)
     const unsigned ktile = smem_addr + stage * C::kStageBytes;
-    const unsigned vtile = ktile + Tl::kBytes;
+    const unsigned b_row = fa.row + ktile, b_tr = fa.tr + ktile, b_tr8 = fa.tr8 + ktile;
 
     f32x16 s[2], dp[2];  // S^T, dP^T: [key block]; a lane holds 16 keys of its query
 #pragma unroll
@@ -546,8 +550,9 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
       for (int i = 0; i < 16; ++i) s[kb][i] = dp[kb][i] = 0.f;
 #pragma unroll
       for (int st = 0; st < Tl::kDSteps; ++st) {
-        s[kb] = mfma_bf16(fa.row_frag(ktile, kb, st), qf[st], s[kb]);
-        dp[kb] = mfma_bf16(fa.row_frag(vtile, kb, st), dof[st], dp[kb]);
+        const unsigned x = (unsigned)xor_here((int)b_row, st << 5);
+        s[kb] = mfma_bf16(fa.row_frag(x, kb, 0), qf[st], s[kb]);
+        dp[kb] = mfma_bf16(fa.row_frag(x, kb, Tl::kBytes), dof[st], dp[kb]);
       }
     }
 
@@ -575,7 +580,8 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int db = 0; db < Tl::kDBlocks; ++db)
-        dq[db] = mfma_bf16(fa.tr_frag(ktile, ks, db), dsb[ks >> 1][ks & 1], dq[db]);
+        dq[db] = mfma_bf16(fa.tr_frag((unsigned)xor_here((int)b_tr, db << 6), (unsigned)xor_here((int)b_tr8, db << 6), ks, 0),
+                           dsb[ks >> 1][ks & 1], dq[db]);
   }
   __syncthreads();
 

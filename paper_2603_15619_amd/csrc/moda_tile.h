@@ -80,17 +80,20 @@ struct FragAddr {
     tr = Tl::off(rr, ch) + (lane & 1) * 8;
     tr8 = Tl::off(rr + 8, ch) + (lane & 1) * 8;
   }
-  // row fragment of the tile at LDS byte address `tile`: rows rb*32 .. rb*32+31, channel step st
-  __device__ __forceinline__ bf16x8 row_frag(unsigned tile, int rb, int st) const {
-    const unsigned a = tile + rb * 32 * Tl::kRowBytes + (unsigned)xor_here(row, st << 5);
-    return *(const bf16x8 __attribute__((address_space(3)))*)(size_t)a;
+  // Addresses are formed as  xor_here(base, constant) + immediate:  `base` = one of the three
+  // registers plus the LDS address of a tile (a multiple of 256, so that the XOR, which only
+  // touches bits 5..7, commutes with that addition), the immediate = row block, and - for the
+  // second tile of a stage, which sits kBytes after the first - the tile.  One XOR thus serves
+  // the fragments at the same place of both tiles of a stage.
+  // row fragment: rows rb*32 .. rb*32+31 of the tile `tile_off` bytes after the one in `xbase`
+  __device__ static __forceinline__ bf16x8 row_frag(unsigned xbase, int rb, int tile_off) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(size_t)(xbase + rb * 32 * Tl::kRowBytes + tile_off);
   }
-  // transposed fragment: rows ks*16 .. ks*16+15, channels db*32 .. db*32+31
-  __device__ __forceinline__ bf16x8 tr_frag(unsigned tile, int ks, int db) const {
-    const unsigned a0 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr, db << 6);
-    const unsigned a1 = tile + ks * 16 * Tl::kRowBytes + (unsigned)xor_here(tr8, db << 6);
-    s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a0);
-    s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)a1);
+  // transposed fragment: rows ks*16 .. ks*16+15 (x0: first read, x8: the rows 8 further on)
+  __device__ static __forceinline__ bf16x8 tr_frag(unsigned x0, unsigned x8, int ks, int tile_off) {
+    const unsigned o = ks * 16 * Tl::kRowBytes + tile_off;
+    s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)(x0 + o));
+    s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(size_t)(x8 + o));
     s16x8 v01 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v01);
   }
