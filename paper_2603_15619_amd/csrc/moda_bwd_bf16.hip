@@ -349,6 +349,8 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
     const float* stat_s = aux + stage * 128;  // (lse2, delta) pairs of the tile's queries
 
     const int key = kw0 + l32;
+    // all 64 queries exist and (when causal) none precedes any of this wave's 32 keys
+    const bool all_visible = q0 + 64 <= T && (!p.causal || q0 >= kw0 + 31);
     // one 32-query block at a time: S, dP (recomputed), P and dS for this lane's key and
     // 16 queries, then dV^T += dO^T P and dK^T += Q^T dS over those 32 queries
 #pragma unroll
@@ -372,6 +374,17 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       __builtin_amdgcn_sched_barrier(0);
+      // Scores of (query, key) pairs that are not visible become -inf, i.e. weight zero.  Only
+      // the diagonal tile and rows past the end have such pairs: everywhere else this block is
+      // skipped (a uniform branch around the comparisons, not a second copy of the loop body).
+      if (!all_visible) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int q = q0 + qb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
+          const bool vis = q < T && (!p.causal || key <= q);
+          s[i] = vis ? s[i] : -INFINITY;
+        }
+      }
       // one 16-query half at a time: P and dS packed to bf16, then straight into the products
       // that contract over those 16 queries (keeps few temporaries alive)
 #pragma unroll
@@ -387,11 +400,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             const int i = b4 * 4 + r;
-            const int q = q0 + qb * 32 + b4 * 8 + hi * 4 + r;
-            const bool vis = q < T && (!p.causal || key <= q);
-            // (a select on the argument, not on the result: the compiler turns the latter into a
-            //  branch around the exponential, one per element)
-            const float pe = fast_exp2(vis ? s[i] * c2 - l4[r] : -INFINITY);
+            const float pe = fast_exp2(s[i] * c2 - l4[r]);
             pv[b2 * 4 + r] = pe;
             dsv[b2 * 4 + r] = pe * (dp[i] - d4[r]);
           }
@@ -558,15 +567,20 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 
     bf16x8 dsb[2][2];
     const int k0 = kt * 64;
+    // every key of the tile exists and is visible to every query of the wave
+    const bool all_visible = k0 + 64 <= T && (!p.causal || k0 + 63 <= qw0);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       float dsv[16];
+      if (!all_visible) {  // (uniform) diagonal tile, keys past the end: invisible pairs get weight zero
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = k0 + kb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
-        const float pe = fast_exp2(key <= lim ? s[kb][i] * c2 - lse2 : -INFINITY);
-        dsv[i] = pe * (dp[kb][i] - delta);
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + kb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
+          s[kb][i] = key <= lim ? s[kb][i] : -INFINITY;
+        }
       }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dsv[i] = fast_exp2(s[kb][i] * c2 - lse2) * (dp[kb][i] - delta);
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         float a[8];
