@@ -112,3 +112,20 @@ def test_new_entry_points_reject_bad_arguments_without_gpu(L):
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 6  # 20 heads per group: 3 launches of 8
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=2))), 1) == 3
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 0) == 1
+
+
+def test_slab_size_limit_without_gpu(L):
+    """One (batch, head) slab of any tensor must stay below 4 GiB (the kernels use 32-bit byte
+    offsets inside a slab): the largest accepted depth cache and the first rejected one."""
+    from paper_2603_15619_amd.binding import MODAShape
+
+    p = ctypes.c_void_p(0x1000)
+    base = dict(B=1, Hq=1, Hk=1, T=65536, d=128, depth_count=1, causal=1, scale=0.0, dtype=1)
+
+    def fwd_status(depth_alloc):
+        s = MODAShape(depth_alloc=depth_alloc, **base)
+        # NULL output pointer: a shape that passes validation stops at the pointer check
+        return L.moda_attn_fwd(p, p, p, p, p, None, p, ctypes.byref(s), None)
+
+    assert fwd_status(255) == 1   # 65536 * 255 * 128 * 2 bytes < 4 GiB: shape accepted (then NULL output)
+    assert fwd_status(256) == 3   # exactly 4 GiB: unsupported
