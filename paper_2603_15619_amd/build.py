@@ -150,7 +150,7 @@ def check_named_acc_registers(src) -> None:
 
 
 # Kernels whose key loop keeps global -> LDS copies in flight while it computes must not
-# touch scratch memory inside a loop: memory operations complete in order, so waiting for a
+# touch scratch memory inside that loop: memory operations complete in order, so waiting for a
 # reload also waits for the copies (measured on the dK/dV kernel: 1.9 ms with 100 bytes of
 # scratch per lane reloaded in the loop, 1.55 ms without).  A value parked in scratch before
 # the loops and fetched after them is harmless.
@@ -169,13 +169,23 @@ def check_no_scratch_in_loops(src, name_part) -> None:
         if name_part not in name:
             continue
         found += 1
-        in_loop = False
+        # the compiler annotates every basic block of a loop with the header of its innermost loop;
+        # the loops that matter are those that issue matrix instructions (the key loops)
+        header, per_line = None, []
         for n, line in body:
-            # the compiler annotates every basic block that belongs to a loop
             if re.match(r"^(\.LBB\d+_\d+:|; %bb\.\d+:)", line):
-                in_loop = "Loop" in line
-            elif in_loop and re.match(r"^\s*scratch_", line):
-                raise RuntimeError("%s:%d: %s touches scratch memory inside a loop: %s"
+                m = re.search(r"Header=(BB\d+_\d+)", line)
+                if m:
+                    header = m.group(1)
+                elif "Loop Header" in line:
+                    header = re.match(r"^\.L(BB\d+_\d+):", line).group(1)
+                else:
+                    header = None
+            per_line.append((n, line, header))
+        hot = {h for _, line, h in per_line if h and re.match(r"^\s*v_mfma", line)}
+        for n, line, h in per_line:
+            if h in hot and re.match(r"^\s*scratch_", line):
+                raise RuntimeError("%s:%d: %s touches scratch memory inside a key loop: %s"
                                    % (asm, n, name, line.strip()))
     if found == 0:
         raise RuntimeError("%s: no kernel named *%s*" % (asm, name_part))
