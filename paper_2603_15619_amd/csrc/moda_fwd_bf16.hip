@@ -1,7 +1,9 @@
 // MoDA attention forward, bf16 inputs, fp32 online-softmax state, gfx950 MFMA.
 //
-// One workgroup = 8 waves (two per SIMD) = one tile of 256 queries of one (b, h); each
-// wave owns 32 queries.  Two waves per SIMD matter: a single wave issues a vector-ALU
+// One workgroup = 8 waves (two per SIMD) = one tile of 256 (position, query head) pairs of
+// one key/value head (256 positions of one head without grouped queries); each wave owns 32
+// of them.  (A second geometry, 4 waves and 2-stage rings, serves small grids.)  Two waves
+// per SIMD matter: a single wave issues a vector-ALU
 // instruction only every ~8 cycles and an exp2 every ~24, two waves together reach
 // ~5.7 and ~9.4 (measured), and the softmax arithmetic of this operator needs about as
 // many vector-ALU cycles as its matrix products need matrix-pipe cycles.
@@ -22,12 +24,15 @@
 // accumulators; score tiles, P and the softmax state live in the 128 vector registers.
 // Tiles above the diagonal are never loaded; only the diagonal tile is masked
 // (Algorithm 1's split into fully visible and boundary blocks).
-// After the sequence loop the accumulators pass through LDS into a row-major
-// mapping (d/8 lanes x 8 channels per query).  There the depth slots of the
-// query's own position -- one contiguous L*d block in the [B,H,T,L,d] layout --
-// are scored with packed dot products and a DPP reduction over those lanes and folded
-// into the SAME running max / normaliser / output (Algorithm 1's third loop and
-// its single final division), and O / LSE are stored with 128-bit accesses.
+// The depth slots of the query's own position -- one contiguous L*d block in the
+// [B,H,T,L,d] layout -- are handled in a row-major mapping (d/8 lanes x 8 channels per
+// query): scored with packed dot products and a DPP reduction over those lanes and folded
+// into the SAME running max / normaliser / output (Algorithm 1's third loop and its single
+// final division).  Every other workgroup does this after the sequence loop (the
+// accumulators pass through LDS into the row-major mapping), the others before it (the
+// row-major state passes through LDS into the accumulators): the result is the same, and the
+// compute units then do not all stream from HBM at the same time.  O / LSE are stored with
+// 128-bit accesses.
 #include <type_traits>
 #include <utility>
 
