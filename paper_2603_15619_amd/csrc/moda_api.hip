@@ -104,6 +104,20 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
     const int gt = atoi(e);
     if (gt >= 1 && waves % gt == 0 && G % gt == 0) p.heads_per_tile = gt;
   }
+  // heads that a die walks together: as many as have their sequence K/V (2 * T * d elements each)
+  // in its 4 MB L2, at least one; a power of two that divides the heads of a die
+  p.head_group = 0;
+  {
+    const long long tile_heads = (long long)s->B * s->Hk * (G / p.heads_per_tile);
+    if (tile_heads % 8 == 0) {
+      const long long per_die = tile_heads / 8;
+      const long long fit = (4ll << 20) / (4ll * s->T * s->d);
+      int hg = 1;
+      while (hg * 2 <= fit && per_die % (hg * 2) == 0) hg *= 2;
+      p.head_group = hg;
+    }
+  }
+  if (const char* e = getenv("MODA_FWD_HEAD_GROUP")) p.head_group = atoi(e);  // experiments
   const int rows = moda::fwd_bf16_tile_rows(waves) / p.heads_per_tile;  // positions per tile
   p.n_qtiles = (s->T + rows - 1) / rows;
 

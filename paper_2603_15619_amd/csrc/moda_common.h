@@ -33,6 +33,7 @@ struct FwdParams {
   float scale_log2;  // scale * log2(e): logits are exponentiated with exp2
   int n_qtiles;      // tiles along the sequence (bf16 kernel: see heads_per_tile)
   int heads_per_tile;  // bf16 kernel: query heads of one group that share a tile (divides Hq/Hk and the waves)
+  int head_group;      // bf16 kernel: heads that one die walks together, tile by tile (0: all its heads)
 };
 
 // Kernel arguments of the backward pass (bf16, Hq == Hk).

@@ -412,14 +412,27 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int GT = p.heads_per_tile;
   const int sub = G / GT;                 // head subsets per group
   const int NBH = p.B * p.Hk * sub;
+  // A die (equal id mod 8) does not walk all its heads tile by tile at once: it takes
+  // head_group of them at a time, heavy tiles first, then the next head_group, so that the
+  // K/V of the heads in progress fit its L2 (measured at T = 65536, 2 heads per die: one at
+  // a time -4 %; at T = 4096, 16 heads per die: two at a time -4 %, one at a time slower
+  // again, because the heaviest tiles of a head then start late).
   int tbh = blockIdx.x % NBH;
+  int tile_idx = blockIdx.x / NBH;
+  if (p.head_group > 0 && NBH % (8 * p.head_group) == 0) {
+    const int die = blockIdx.x & 7, r = blockIdx.x >> 3;       // r-th workgroup of this die
+    const int per_group = p.head_group * p.n_qtiles;
+    const int grp = r / per_group, w = r % per_group;
+    tile_idx = w / p.head_group;
+    tbh = (grp * p.head_group + w % p.head_group) * 8 + die;
+  }
   if (sub > 1 && NBH % (8 * sub) == 0) {
     // the head subsets of one group read the same K/V: the ids that land on one die (equal id
     // mod 8) walk over the subsets of one group first, so that one L2 serves the group
     const int die = tbh & 7, m = tbh >> 3;
     tbh = ((m / sub) * 8 + die) * sub + m % sub;
   }
-  const int qt = p.n_qtiles - 1 - blockIdx.x / NBH;
+  const int qt = p.n_qtiles - 1 - tile_idx;
   const int bg = tbh / sub;               // (batch, key/value head)
   const int b = bg / p.Hk;
   const int g = bg - b * p.Hk;
