@@ -310,6 +310,21 @@ def main():
     achieved = flops / (ms_kernel * 1e-3) / 1e12
     esz = 2 if dtype == "bf16" else 4
     depth_bytes = 2.0 * B * Hk * T * L * d * esz
+    # Which roof bounds this workload: the time its algorithmic FLOPs need at the matrix (or, for
+    # fp32, vector) peak against the time its algorithmic bytes need at the HBM peak.
+    alg_bytes = esz * (B * T * d * (2 * Hq + 2 * Hk) + 2.0 * B * Hk * T * L * d) + 4.0 * B * Hq * T
+    common = {"traffic": measured_traffic(args.workload, "fwd"),
+              "kernel": ("moda_fwd_bf16_kernel<%d, 8>" % d) if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
+              "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
+              "flops_per_launch": flops, "bytes_per_launch": alg_bytes}
+    if alg_bytes / 8.0e12 > flops / (PEAK_TFLOPS[dtype] * 1e12):
+        gbps = alg_bytes / (ms_kernel * 1e-3) / 1e9
+        roofline = dict({"bound": "hbm", "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
+                         "frac": round(gbps / 8000.0, 4)}, **common)
+    else:
+        roofline = dict({"bound": "mfma" if dtype == "bf16" else "alu", "achieved": round(achieved, 2),
+                         "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                         "frac": round(achieved / PEAK_TFLOPS[dtype], 4)}, **common)
     out = {
         "metric": "MoDA attn fwd TFLOP/s + ratio to own causal FA kernel at T=64K, 1 GPU",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -317,13 +332,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: B=%d Hq=%d Hk=%d T=%d d=%d depth_count=%d causal fwd" %
                                (args.workload, B, Hq, Hk, T, d, L)},
-        "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "achieved": round(achieved, 2),
-                     "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_TFLOPS[dtype], 4),
-                     "traffic": measured_traffic(args.workload, "fwd"),
-                     "kernel": ("moda_fwd_bf16_kernel<%d, 8>" % d) if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
-                     "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
-                     "flops_per_launch": flops},
+        "roofline": roofline,
     }
     if fa is not None:
         fa_flops = fwd_flops(B, Hq, T, d, 0)
