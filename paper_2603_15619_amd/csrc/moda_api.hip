@@ -40,6 +40,18 @@ int fwd_waves_per_workgroup(const moda_shape* s) {
   return tiles8 < 256 ? 4 : 8;
 }
 
+// Heads that one die (workgroup ids equal mod 8) walks together, tile by tile: as many as have
+// their streamed tensors (2 * T * d bf16 elements each: K and V, or Q and dO) in its 4 MB L2, at
+// least one; a power of two that divides the heads of a die.  0: the ids cannot be dealt that way.
+int heads_per_die_at_a_time(long long n_heads, int T, int d) {
+  if (n_heads % 8 != 0) return 0;
+  const long long per_die = n_heads / 8;
+  const long long fit = (4ll << 20) / (4ll * T * d);
+  int hg = 1;
+  while (hg * 2 <= fit && per_die % (hg * 2) == 0) hg *= 2;
+  return hg;
+}
+
 float resolve_scale(const moda_shape* s) {
   return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
 }
@@ -104,19 +116,7 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
     const int gt = atoi(e);
     if (gt >= 1 && waves % gt == 0 && G % gt == 0) p.heads_per_tile = gt;
   }
-  // heads that a die walks together: as many as have their sequence K/V (2 * T * d elements each)
-  // in its 4 MB L2, at least one; a power of two that divides the heads of a die
-  p.head_group = 0;
-  {
-    const long long tile_heads = (long long)s->B * s->Hk * (G / p.heads_per_tile);
-    if (tile_heads % 8 == 0) {
-      const long long per_die = tile_heads / 8;
-      const long long fit = (4ll << 20) / (4ll * s->T * s->d);
-      int hg = 1;
-      while (hg * 2 <= fit && per_die % (hg * 2) == 0) hg *= 2;
-      p.head_group = hg;
-    }
-  }
+  p.head_group = heads_per_die_at_a_time((long long)s->B * s->Hk * (G / p.heads_per_tile), s->T, s->d);
   if (const char* e = getenv("MODA_FWD_HEAD_GROUP")) p.head_group = atoi(e);  // experiments
   const int rows = moda::fwd_bf16_tile_rows(waves) / p.heads_per_tile;  // positions per tile
   p.n_qtiles = (s->T + rows - 1) / rows;
@@ -202,6 +202,7 @@ moda_status moda_attn_bwd(const void* Q, const void* Kseq, const void* Vseq, con
   p.causal = s->causal;
   p.scale = resolve_scale(s);
   p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.head_group = heads_per_die_at_a_time((long long)s->B * s->Hk, s->T, s->d);
   hipError_t e = moda::launch_bwd_bf16(p, s->d, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MODA_OK : MODA_ERR_LAUNCH;
 }

@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   const int T = p.T;
   const int BHk = p.B * p.Hk;
   int bg, jt;  // (batch, key/value head); key tiles in natural order: the first ones see the most queries
-  head_blocked_id((int)blockIdx.x, BHk, (T + 127) / 128, bg, jt);
+  head_blocked_id((int)blockIdx.x, BHk, (T + 127) / 128, bg, jt, p.head_group);
   const int j0 = jt * 128;
   const int kw0 = j0 + wave * 32;
   const int G = p.Hq / p.Hk;        // query heads per key/value head: their gradients add up here
@@ -473,7 +473,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int BH = p.B * p.Hq;
   const int n_qt = (T + kQT - 1) / kQT;
   int bh, tile_idx;
-  head_blocked_id((int)blockIdx.x, BH, n_qt, bh, tile_idx);
+  head_blocked_id((int)blockIdx.x, BH, n_qt, bh, tile_idx, p.head_group);
   const int qt = n_qt - 1 - tile_idx;  // heavy (late) query tiles first
   const int q0 = qt * kQT;
   const int qw0 = q0 + wave * 32;

@@ -57,18 +57,22 @@ struct BwdParams {
   int causal;
   float scale;
   float scale_log2;
+  int head_group;  // heads that one die walks together, tile by tile (see head_blocked_id)
 };
 
 // Workgroup id -> (head index, tile position in the walking order).  Ids are dealt round-robin
 // to the 8 dies (each with its own L2).  With `n_heads` a multiple of 8, die x takes the heads
-// x, x + 8, x + 16, ... ONE AFTER THE OTHER, each with all its `n_tiles` tiles, instead of a tile
+// x, x + 8, x + 16, ... `group` AT A TIME, each with all its `n_tiles` tiles, instead of a tile
 // of every head at a time: the workgroups that run together on a die then stream the K/V (or
-// Q/dO) of one or two heads, which its L2 holds, and not of n_heads / 8.
-__device__ __forceinline__ void head_blocked_id(int id, int n_heads, int n_tiles, int& head, int& tile) {
-  if (n_heads % 8 == 0) {
+// Q/dO) of a few heads, which its L2 holds, and not of n_heads / 8.
+__device__ __forceinline__ void head_blocked_id(int id, int n_heads, int n_tiles, int& head, int& tile,
+                                                int group = 1) {
+  if (group > 0 && n_heads % (8 * group) == 0) {
     const int die = id & 7, r = id >> 3;
-    head = (r / n_tiles) * 8 + die;
-    tile = r % n_tiles;
+    const int per_group = group * n_tiles;
+    const int grp = r / per_group, w = r % per_group;
+    tile = w / group;
+    head = (grp * group + w % group) * 8 + die;
   } else {
     head = id % n_heads;
     tile = id / n_heads;
