@@ -34,6 +34,7 @@ WORKLOADS = {
     "sweep": None,             # BASELINE configs[3]: B=4 H=16 d=128, T x depth_count grid
     "paper_table2": None,      # the paper's Table 2 shapes (d=64, grouped queries, 64..256 slots), fwd+bwd
     "decode": None,            # one new token per sequence against a 64K sequence cache
+    "append": None,            # the depth stream's write step (a strided copy)
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16 / fp32 vector
 
@@ -176,6 +177,27 @@ def run_decode(args):
                       "warmup": args.warmup, "points": points}))
 
 
+def run_append(args):
+    """Write step: a layer's K/V [B,Hk,T,d] into one slot of the cache; every byte read once, written once."""
+    from paper_2603_15619_amd import moda_depth_append, synth
+
+    points = []
+    for (B, Hk, T, d, La) in ((8, 16, 4096, 128, 16), (1, 16, 65536, 128, 16), (1, 8, 65536, 64, 64)):
+        inp = synth.make_inputs(B, Hk, Hk, T, d, 0, dtype="bf16", seed=8, device="cuda")
+        Kd = torch.zeros((B, Hk, T, La, d), dtype=torch.bfloat16, device="cuda")
+        Vd = torch.zeros_like(Kd)
+        fn = lambda: moda_depth_append(inp["Kseq"], inp["Vseq"], Kd, Vd, La // 2)
+        ms, ms_k, _ = time_calls(fn, args.steps, args.warmup)
+        moved = 2 * 2.0 * B * Hk * T * d * 2  # K and V, read + written
+        points.append({"B": B, "Hk": Hk, "T": T, "d": d, "depth_alloc": La, "ms": round(ms, 4),
+                       "hbm_gbps": round(moved / (ms_k * 1e-3) / 1e9, 1),
+                       "frac_of_8TBps": round(moved / (ms_k * 1e-3) / 1e9 / 8000.0, 4)})
+        del inp, Kd, Vd
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "MoDA depth-stream write step (moda_depth_append), bf16", "steps": args.steps,
+                      "warmup": args.warmup, "points": points}))
+
+
 def run_backward(args, B, Hq, Hk, T, d, L, dtype):
     from paper_2603_15619_amd import moda_attn_bwd, moda_attn_fwd, synth
 
@@ -277,6 +299,8 @@ def main():
         return run_paper_table2(args)
     if args.workload == "decode":
         return run_decode(args)
+    if args.workload == "append":
+        return run_append(args)
     B, Hq, Hk, T, d, L, dtype = WORKLOADS[args.workload]
     if args.depth_count is not None:
         L = args.depth_count

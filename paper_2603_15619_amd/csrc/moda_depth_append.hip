@@ -8,19 +8,35 @@
 
 namespace moda {
 
+constexpr int kAppendPerThread = 4;  // 16-byte chunks of K (and of V) per thread, all loaded before any store
+
 __global__ __launch_bounds__(256) void moda_depth_append_kernel(const char* __restrict__ K, const char* __restrict__ V,
                                                                 char* __restrict__ Kd, char* __restrict__ Vd,
                                                                 long long n_chunks, int chunks_per_row,
                                                                 int depth_alloc, int slot) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;  // 16-byte chunk of K (and of V)
-  if (i >= n_chunks) return;
-  const long long row = i / chunks_per_row;
-  const int c = (int)(i - row * chunks_per_row);
-  const size_t dst = ((size_t)(row * depth_alloc + slot) * chunks_per_row + c) * 16;
-  const u32x4 kv = __builtin_nontemporal_load((const u32x4*)(K + (size_t)i * 16));
-  const u32x4 vv = __builtin_nontemporal_load((const u32x4*)(V + (size_t)i * 16));
-  __builtin_nontemporal_store(kv, (u32x4*)(Kd + dst));
-  __builtin_nontemporal_store(vv, (u32x4*)(Vd + dst));
+  // chunk i of this thread: (block * kAppendPerThread + u) * 256 + thread, so that a wave's
+  // accesses stay contiguous
+  const long long base = (long long)blockIdx.x * kAppendPerThread * 256 + threadIdx.x;
+  u32x4 kv[kAppendPerThread], vv[kAppendPerThread];
+#pragma unroll
+  for (int u = 0; u < kAppendPerThread; ++u) {
+    const long long i = base + u * 256;
+    if (i < n_chunks) {
+      kv[u] = __builtin_nontemporal_load((const u32x4*)(K + (size_t)i * 16));
+      vv[u] = __builtin_nontemporal_load((const u32x4*)(V + (size_t)i * 16));
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kAppendPerThread; ++u) {
+    const long long i = base + u * 256;
+    if (i < n_chunks) {
+      const long long row = i / chunks_per_row;
+      const int c = (int)(i - row * chunks_per_row);
+      const size_t dst = ((size_t)(row * depth_alloc + slot) * chunks_per_row + c) * 16;
+      __builtin_nontemporal_store(kv[u], (u32x4*)(Kd + dst));
+      __builtin_nontemporal_store(vv[u], (u32x4*)(Vd + dst));
+    }
+  }
 }
 
 hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void* Vdepth, long long rows,
@@ -28,7 +44,7 @@ hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void*
   if (row_bytes % 16 != 0) return hipErrorInvalidValue;
   const int cpr = row_bytes / 16;
   const long long n_chunks = rows * cpr;
-  const long long blocks = (n_chunks + 255) / 256;
+  const long long blocks = (n_chunks + 256 * kAppendPerThread - 1) / (256 * kAppendPerThread);
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(moda_depth_append_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const char*)K,
                      (const char*)V, (char*)Kdepth, (char*)Vdepth, n_chunks, cpr, depth_alloc, slot);
