@@ -637,7 +637,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 // launch within its group); every launch after the first adds to the dKdepth / dVdepth the
 // previous ones wrote (read, add in fp32, round again).
 template <int D, int GT>
-__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_kernel(BwdParams p, int head0) {
+__global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p, int head0) {
   constexpr int LPR = D / 8, ROWS = 256 / LPR, RB = D * 2;
   const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
   const int tid = threadIdx.x, l16 = tid % LPR;
