@@ -159,11 +159,17 @@ NO_SCRATCH_IN_LOOPS = (("moda_bwd_bf16.hip", "moda_bwd_dkdv_kernel"), ("moda_bwd
 
 
 def check_no_scratch_in_loops(src, name_part) -> None:
-    import re
-
     asm = os.path.join(OBJ, os.path.basename(src)[:-4] + ".s")
     subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", asm], check=True,
                    stderr=subprocess.DEVNULL)
+    scan_scratch_in_key_loops(asm, name_part)
+
+
+def scan_scratch_in_key_loops(asm, name_part) -> None:
+    """Raises if a kernel of assembly file `asm` whose name contains `name_part` touches scratch
+    memory inside a loop that issues matrix instructions."""
+    import re
+
     found = 0
     for name, body in _kernel_bodies(asm):
         if name_part not in name:
