@@ -472,13 +472,16 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int T = p.T;
   const int BH = p.B * p.Hq;
   const int n_qt = (T + kQT - 1) / kQT;
-  int bh, tile_idx;
-  head_blocked_id((int)blockIdx.x, BH, n_qt, bh, tile_idx, p.head_group);
-  const int qt = n_qt - 1 - tile_idx;  // heavy (late) query tiles first
+  // Ids are dealt to the dies by key/value head (see head_blocked_id): the G query heads of a
+  // group stream the same K/V, so a die takes a group's heads one right after the other, query
+  // tile by query tile (heavy, i.e. late, tiles first).
+  const int G = p.Hq / p.Hk;
+  int bg, tile_idx;  // (batch, key/value head); position in the walk over (query tile, head of the group)
+  head_blocked_id((int)blockIdx.x, p.B * p.Hk, n_qt * G, bg, tile_idx, p.head_group);
+  const int qt = n_qt - 1 - tile_idx / G;
+  const int bh = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G + tile_idx % G;
   const int q0 = qt * kQT;
   const int qw0 = q0 + wave * 32;
-  const int G = p.Hq / p.Hk;
-  const int bg = (bh / p.Hq) * p.Hk + (bh % p.Hq) / G;  // (batch, key/value head) of this query head
 
   const char* Qb = (const char*)p.Q + (size_t)bh * T * Tl::kRowBytes;
   const char* Kb = (const char*)p.Kseq + (size_t)bg * T * Tl::kRowBytes;
