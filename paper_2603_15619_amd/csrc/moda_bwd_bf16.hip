@@ -470,7 +470,6 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int T = p.T;
-  const int BH = p.B * p.Hq;
   const int n_qt = (T + kQT - 1) / kQT;
   // Ids are dealt to the dies by key/value head (see head_blocked_id): the G query heads of a
   // group stream the same K/V, so a die takes a group's heads one right after the other, query
@@ -495,7 +494,7 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const float c2 = p.scale_log2;
   unsigned char* xw = smem + wave * C::kXWave;  // this wave's fp32 exchange buffer (overlaps the ring)
   constexpr int LPR = Tl::kChunks, RPS = 64 / LPR, NIT = 32 / RPS;
-  const int L = p.depth_count, La = p.depth_alloc;
+  const int La = p.depth_alloc;
 
   // The depth-slot gradients and the depth share of dQ were computed before this kernel (by
   // the dK/dV kernel, or by moda_bwd_depth_gqa_kernel with grouped queries); the share is in
