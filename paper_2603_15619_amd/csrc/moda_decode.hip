@@ -17,7 +17,6 @@
 namespace moda {
 
 constexpr int kDecWaves = 4;
-constexpr int kDecMaxG = 8;  // query heads handled together (register budget); larger groups loop
 
 struct DecodeParams {
   const void* Q;       // [B, Hq, d]
