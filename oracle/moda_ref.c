@@ -320,6 +320,126 @@ int moda_ref_bwd_f64(const double* Q, const double* Kseq, const double* Vseq,
 }
 
 /*
+ * Rounding-noise scale of the backward (an analysis helper for the parity
+ * tests' tolerance; the paper gives neither a backward algorithm nor an error
+ * figure for it, Table 2 only times it).
+ *
+ * Model: an implementation of the formulas of moda_ref_bwd_f64 that
+ *   (a) rounds every softmax weight p_c and every logit gradient e_c, each
+ *       (query, key) pair independently, with a relative error of standard
+ *       deviation u before the products that sum over queries or keys, and
+ *   (b) receives an output o of the forward whose elements carry independent
+ *       relative errors of standard deviation u (the forward's output
+ *       rounding), so that delta = <g, o> is off by a random amount of
+ *       standard deviation u * D_t, D_t = sqrt(sum_k (g_k o_k)^2), the same
+ *       amount for every key of the query (e_c is then off by -p_c times it).
+ * To first order in u the error of each gradient element is a sum of
+ * independent terms; this function returns its standard deviation for u = 1:
+ *     nV_c[k]^2 = sum_t (p_tc g_t[k])^2
+ *     nK_c[k]^2 = scale^2 sum_t ((e_tc q_t[k])^2 + (p_tc D_t q_t[k])^2)
+ *     nQ_t[k]^2 = scale^2 (sum_c (e_tc k_c[k])^2 + (D_t sum_c p_tc k_c[k])^2)
+ * (sums over t run over the queries, and the G query heads, that see key c).
+ * Arguments and layouts as in moda_ref_bwd_f64; any output may be NULL.
+ */
+int moda_ref_bwd_noise_f64(const double* Q, const double* Kseq, const double* Vseq,
+                           const double* Kdepth, const double* Vdepth, const double* dO, double* nQ,
+                           double* nKseq, double* nVseq, double* nKdepth, double* nVdepth, int B,
+                           int Hq, int Hk, int T, int d, int depth_alloc, int depth_count, int causal,
+                           double scale) {
+  ref_shape s = {B, Hq, Hk, T, d, depth_alloc, depth_count, causal, scale};
+  if (!shape_ok(&s)) return 1;
+  if (!Q || !Kseq || !Vseq || !dO) return 1;
+  if (depth_count > 0 && (!Kdepth || !Vdepth)) return 1;
+  const int G = Hq / Hk;
+  int fail = 0;
+#pragma omp parallel
+  {
+    size_t nmax = (size_t)T + depth_count + 1;
+    double* logit = (double*)malloc(sizeof(double) * nmax);
+    const double** val = (const double**)malloc(sizeof(double*) * nmax);
+    double* w = (double*)malloc(sizeof(double) * nmax);
+    double* o = (double*)malloc(sizeof(double) * (size_t)d);
+    double* kbar = (double*)malloc(sizeof(double) * (size_t)d);
+    if (!logit || !val || !w || !o || !kbar) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int bg = 0; bg < B * Hk; ++bg) {
+        int b = bg / Hk, g = bg % Hk;
+        const double* ks = Kseq + (size_t)bg * T * d;
+        const double* vs = Vseq + (size_t)bg * T * d;
+        double* nks = nKseq ? nKseq + (size_t)bg * T * d : NULL;
+        double* nvs = nVseq ? nVseq + (size_t)bg * T * d : NULL;
+        size_t nd = (size_t)T * depth_alloc * d;
+        double* nkd = (nKdepth && depth_alloc > 0) ? nKdepth + (size_t)bg * nd : NULL;
+        double* nvd = (nVdepth && depth_alloc > 0) ? nVdepth + (size_t)bg * nd : NULL;
+        /* the variances are summed in place; the square root is taken at the end */
+        if (nks) memset(nks, 0, sizeof(double) * (size_t)T * d);
+        if (nvs) memset(nvs, 0, sizeof(double) * (size_t)T * d);
+        if (nkd) memset(nkd, 0, sizeof(double) * nd);
+        if (nvd) memset(nvd, 0, sizeof(double) * nd);
+        for (int hh = 0; hh < G; ++hh) {
+          int h = g * G + hh;
+          for (int t = 0; t < T; ++t) {
+            size_t qoff = ((size_t)(b * Hq + h) * T + t) * d;
+            const double* q = Q + qoff;
+            const double* go = dO + qoff;
+            size_t doff_local = (size_t)t * depth_alloc * d;
+            const double* kd = depth_count ? Kdepth + (size_t)bg * nd + doff_local : NULL;
+            const double* vd = depth_count ? Vdepth + (size_t)bg * nd + doff_local : NULL;
+            int n_seq = causal ? t + 1 : T;
+            double lse;
+            one_query(q, ks, vs, n_seq, kd, vd, depth_count, d, scale, logit, val, o, &lse, w);
+            double delta = dot(go, o, d);
+            double D2 = 0.0;
+            for (int k = 0; k < d; ++k) D2 += (go[k] * o[k]) * (go[k] * o[k]);
+            for (int k = 0; k < d; ++k) kbar[k] = 0.0;
+            double* nq = nQ ? nQ + qoff : NULL;
+            if (nq)
+              for (int k = 0; k < d; ++k) nq[k] = 0.0;
+            for (int c = 0; c < n_seq + depth_count; ++c) {
+              const double* kc;
+              double *nkc, *nvc;
+              if (c < n_seq) {
+                kc = ks + (size_t)c * d;
+                nkc = nks ? nks + (size_t)c * d : NULL;
+                nvc = nvs ? nvs + (size_t)c * d : NULL;
+              } else {
+                size_t so = doff_local + (size_t)(c - n_seq) * d;
+                kc = kd + (size_t)(c - n_seq) * d;
+                nkc = nkd ? nkd + so : NULL;
+                nvc = nvd ? nvd + so : NULL;
+              }
+              double e = w[c] * (dot(go, val[c], d) - delta);
+              for (int k = 0; k < d; ++k) {
+                kbar[k] += w[c] * kc[k];
+                if (nvc) nvc[k] += (w[c] * go[k]) * (w[c] * go[k]);
+                if (nq) nq[k] += (scale * e * kc[k]) * (scale * e * kc[k]);
+                if (nkc) nkc[k] += (scale * q[k]) * (scale * q[k]) * (e * e + w[c] * w[c] * D2);
+              }
+            }
+            if (nq)
+              for (int k = 0; k < d; ++k)
+                nq[k] = sqrt(nq[k] + (scale * kbar[k]) * (scale * kbar[k]) * D2);
+          }
+        }
+        if (nks) for (size_t i = 0; i < (size_t)T * d; ++i) nks[i] = sqrt(nks[i]);
+        if (nvs) for (size_t i = 0; i < (size_t)T * d; ++i) nvs[i] = sqrt(nvs[i]);
+        if (nkd) for (size_t i = 0; i < nd; ++i) nkd[i] = sqrt(nkd[i]);
+        if (nvd) for (size_t i = 0; i < nd; ++i) nvd[i] = sqrt(nvd[i]);
+      }
+    }
+    free(logit);
+    free((void*)val);
+    free(w);
+    free(o);
+    free(kbar);
+  }
+  return fail;
+}
+
+/*
  * Backward, row-local gradients only, for a list of positions rows[0..n_rows):
  * dQ_rows [B,Hq,n_rows,d] and dKdepth_rows/dVdepth_rows
  * [B,Hk,n_rows,depth_alloc,d] (either may be NULL).  These depend only on the
@@ -401,6 +521,102 @@ int moda_ref_bwd_rows_f64(const double* Q_rows, const double* Kseq, const double
     free((void*)val);
     free(w);
     free(o);
+  }
+  return fail;
+}
+
+/*
+ * Rounding-noise scale (see moda_ref_bwd_noise_f64) of the row-local
+ * gradients for a list of positions; arguments and layouts as in
+ * moda_ref_bwd_rows_f64.
+ */
+int moda_ref_bwd_noise_rows_f64(const double* Q_rows, const double* Kseq, const double* Vseq,
+                                const double* Kdepth_rows, const double* Vdepth_rows,
+                                const double* dO_rows, const int* rows, int n_rows, double* nQ_rows,
+                                double* nKdepth_rows, double* nVdepth_rows, int B, int Hq, int Hk,
+                                int T, int d, int depth_alloc, int depth_count, int causal,
+                                double scale) {
+  ref_shape s = {B, Hq, Hk, T, d, depth_alloc, depth_count, causal, scale};
+  if (!shape_ok(&s) || n_rows < 0) return 1;
+  if (!Q_rows || !Kseq || !Vseq || !dO_rows || (n_rows > 0 && !rows)) return 1;
+  if (depth_count > 0 && (!Kdepth_rows || !Vdepth_rows)) return 1;
+  for (int r = 0; r < n_rows; ++r)
+    if (rows[r] < 0 || rows[r] >= T) return 1;
+  const int G = Hq / Hk;
+  int fail = 0;
+#pragma omp parallel
+  {
+    size_t nmax = (size_t)T + depth_count + 1;
+    double* logit = (double*)malloc(sizeof(double) * nmax);
+    const double** val = (const double**)malloc(sizeof(double*) * nmax);
+    double* w = (double*)malloc(sizeof(double) * nmax);
+    double* o = (double*)malloc(sizeof(double) * (size_t)d);
+    double* kbar = (double*)malloc(sizeof(double) * (size_t)d);
+    if (!logit || !val || !w || !o || !kbar) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 4)
+      for (long long idx = 0; idx < (long long)B * Hk * n_rows; ++idx) {
+        int r = (int)(idx % n_rows);
+        int bg = (int)(idx / n_rows);
+        int b = bg / Hk, g = bg % Hk;
+        int t = rows[r];
+        const double* ks = Kseq + (size_t)bg * T * d;
+        const double* vs = Vseq + (size_t)bg * T * d;
+        size_t doff = ((size_t)bg * n_rows + r) * (size_t)depth_alloc * d;
+        const double* kd = depth_count ? Kdepth_rows + doff : NULL;
+        const double* vd = depth_count ? Vdepth_rows + doff : NULL;
+        size_t nslot = (size_t)depth_alloc * d;
+        if (depth_alloc > 0) {
+          if (nKdepth_rows) memset(nKdepth_rows + doff, 0, sizeof(double) * nslot);
+          if (nVdepth_rows) memset(nVdepth_rows + doff, 0, sizeof(double) * nslot);
+        }
+        int n_seq = causal ? t + 1 : T;
+        for (int hh = 0; hh < G; ++hh) {
+          int h = g * G + hh;
+          size_t qoff = ((size_t)(b * Hq + h) * n_rows + r) * d;
+          const double* q = Q_rows + qoff;
+          const double* go = dO_rows + qoff;
+          double lse;
+          one_query(q, ks, vs, n_seq, kd, vd, depth_count, d, scale, logit, val, o, &lse, w);
+          double delta = dot(go, o, d);
+          double D2 = 0.0;
+          for (int k = 0; k < d; ++k) D2 += (go[k] * o[k]) * (go[k] * o[k]);
+          for (int k = 0; k < d; ++k) kbar[k] = 0.0;
+          double* nq = nQ_rows ? nQ_rows + qoff : NULL;
+          if (nq)
+            for (int k = 0; k < d; ++k) nq[k] = 0.0;
+          for (int c = 0; c < n_seq + depth_count; ++c) {
+            double e = w[c] * (dot(go, val[c], d) - delta);
+            const double* kc = c < n_seq ? ks + (size_t)c * d : kd + (size_t)(c - n_seq) * d;
+            for (int k = 0; k < d; ++k) {
+              kbar[k] += w[c] * kc[k];
+              if (nq) nq[k] += (scale * e * kc[k]) * (scale * e * kc[k]);
+            }
+            if (c >= n_seq) {
+              size_t so = doff + (size_t)(c - n_seq) * d;
+              for (int k = 0; k < d; ++k) {
+                if (nKdepth_rows)
+                  nKdepth_rows[so + k] += (scale * q[k]) * (scale * q[k]) * (e * e + w[c] * w[c] * D2);
+                if (nVdepth_rows) nVdepth_rows[so + k] += (w[c] * go[k]) * (w[c] * go[k]);
+              }
+            }
+          }
+          if (nq)
+            for (int k = 0; k < d; ++k) nq[k] = sqrt(nq[k] + (scale * kbar[k]) * (scale * kbar[k]) * D2);
+        }
+        if (depth_alloc > 0) {
+          if (nKdepth_rows) for (size_t i = 0; i < nslot; ++i) nKdepth_rows[doff + i] = sqrt(nKdepth_rows[doff + i]);
+          if (nVdepth_rows) for (size_t i = 0; i < nslot; ++i) nVdepth_rows[doff + i] = sqrt(nVdepth_rows[doff + i]);
+        }
+      }
+    }
+    free(logit);
+    free((void*)val);
+    free(w);
+    free(o);
+    free(kbar);
   }
   return fail;
 }

@@ -26,7 +26,8 @@ def lib():
     if _lib is None:
         _lib = ctypes.CDLL(build_oracle(force=False))
         for name in ("moda_ref_fwd_f64", "moda_ref_fwd_rows_f64", "moda_ref_weights_f64",
-                     "moda_ref_bwd_f64", "moda_ref_bwd_rows_f64", "moda_ref_num_threads"):
+                     "moda_ref_bwd_f64", "moda_ref_bwd_rows_f64", "moda_ref_bwd_noise_f64",
+                     "moda_ref_bwd_noise_rows_f64", "moda_ref_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -147,6 +148,46 @@ def bwd_rows(Q_rows, Kseq, Vseq, Kdepth_rows, Vdepth_rows, dO_rows, rows, depth_
     if rc != 0:
         raise ValueError("moda_ref_bwd_rows_f64 rejected its arguments")
     return dQ, dKd, dVd
+
+
+def bwd_noise(Q, Kseq, Vseq, Kdepth, Vdepth, dO, depth_count=None, causal=True, scale=None):
+    """Rounding-noise scale of every gradient element (same shapes as bwd's results): the
+    standard deviation, per unit relative rounding error, of the error of an implementation
+    that rounds the softmax weights, the logit gradients and the forward's output before it
+    sums (first-order model, see moda_ref_bwd_noise_f64 in the C file)."""
+    Q, Kseq, Vseq, Kdepth, Vdepth, dO = map(_f64, (Q, Kseq, Vseq, Kdepth, Vdepth, dO))
+    B, Hq, Hk, T, d, da, dc = _dims(Q, Kseq, Kdepth, depth_count)
+    nQ = np.empty_like(Q)
+    nK = np.empty_like(Kseq)
+    nV = np.empty_like(Vseq)
+    nKd = None if Kdepth is None else np.empty_like(Kdepth)
+    nVd = None if Vdepth is None else np.empty_like(Vdepth)
+    rc = lib().moda_ref_bwd_noise_f64(_p(Q), _p(Kseq), _p(Vseq), _p(Kdepth), _p(Vdepth), _p(dO), _p(nQ),
+                                      _p(nK), _p(nV), _p(nKd), _p(nVd), B, Hq, Hk, T, d, da, dc,
+                                      int(bool(causal)), ctypes.c_double(_scale(scale, d)))
+    if rc != 0:
+        raise ValueError("moda_ref_bwd_noise_f64 rejected its arguments")
+    return nQ, nK, nV, nKd, nVd
+
+
+def bwd_noise_rows(Q_rows, Kseq, Vseq, Kdepth_rows, Vdepth_rows, dO_rows, rows, depth_count=None,
+                   causal=True, scale=None):
+    """Rounding-noise scale of the row-local gradients (nQ_rows, nKdepth_rows, nVdepth_rows)."""
+    Q_rows, Kseq, Vseq, Kdepth_rows, Vdepth_rows, dO_rows = map(
+        _f64, (Q_rows, Kseq, Vseq, Kdepth_rows, Vdepth_rows, dO_rows))
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    B, Hq, Hk, T, d, da, dc = _dims(Q_rows, Kseq, Kdepth_rows, depth_count)
+    R = rows.shape[0]
+    nQ = np.empty_like(Q_rows)
+    nKd = None if Kdepth_rows is None else np.empty_like(Kdepth_rows)
+    nVd = None if Vdepth_rows is None else np.empty_like(Vdepth_rows)
+    rc = lib().moda_ref_bwd_noise_rows_f64(_p(Q_rows), _p(Kseq), _p(Vseq), _p(Kdepth_rows),
+                                           _p(Vdepth_rows), _p(dO_rows), rows.ctypes.data_as(_ip), R,
+                                           _p(nQ), _p(nKd), _p(nVd), B, Hq, Hk, T, d, da, dc,
+                                           int(bool(causal)), ctypes.c_double(_scale(scale, d)))
+    if rc != 0:
+        raise ValueError("moda_ref_bwd_noise_rows_f64 rejected its arguments")
+    return nQ, nKd, nVd
 
 
 def depth_append(Kdepth, Vdepth, K, V, slot):

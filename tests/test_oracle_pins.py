@@ -323,6 +323,105 @@ def test_P10_logit_gradients_sum_to_zero():
     np.testing.assert_allclose(dQ, 0.0, atol=1e-13)
 
 
+# ------------------------------ backward: rounding-noise scale ---------------------------------
+def _dense_backward(Q, K, V, Kd, Vd, dO, L, causal, scale, u=0.0, rng=None):
+    """Backward in the dense flattened form (one (b, kv head) at a time), optionally with the
+    rounding model of moda_ref_bwd_noise_f64 injected: independent relative errors of standard
+    deviation u on every weight, every logit gradient and every element of the forward's output."""
+    B, Hq, T, d = Q.shape
+    Hk = K.shape[1]
+    G = Hq // Hk
+    seq, dep = alg1_masks(T, G, L, causal)
+    mask = np.concatenate([seq, dep], axis=1)
+    noise = (lambda shape: 1.0 + u * rng.standard_normal(shape)) if u else (lambda shape: 1.0)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    dKd = None if Kd is None else np.zeros_like(Kd)
+    dVd = None if Vd is None else np.zeros_like(Vd)
+    for b in range(B):
+        for g in range(Hk):
+            flat = lambda X: X[b, g * G:(g + 1) * G].transpose(1, 0, 2).reshape(T * G, d)
+            q, go = flat(Q), flat(dO)
+            keys, vals = K[b, g], V[b, g]
+            if L:
+                keys = np.concatenate([keys, Kd[b, g, :, :L].reshape(T * L, d)])
+                vals = np.concatenate([vals, Vd[b, g, :, :L].reshape(T * L, d)])
+            logit = np.where(mask, scale * q @ keys.T, -np.inf)
+            P = np.exp(logit - logit.max(axis=1, keepdims=True))
+            P /= P.sum(axis=1, keepdims=True)
+            O = (P @ vals) * noise((T * G, d))
+            delta = (go * O).sum(axis=1, keepdims=True)
+            E = P * (go @ vals.T - delta) * noise(P.shape)
+            Pr = P * noise(P.shape)
+            gq = scale * E @ keys
+            gk = scale * E.T @ q
+            gv = Pr.T @ go
+            dQ[b, g * G:(g + 1) * G] = gq.reshape(T, G, d).transpose(1, 0, 2)
+            dK[b, g], dV[b, g] = gk[:T], gv[:T]
+            if L:
+                dKd[b, g, :, :L] = gk[T:].reshape(T, L, d)
+                dVd[b, g, :, :L] = gv[T:].reshape(T, L, d)
+    return dQ, dK, dV, dKd, dVd
+
+
+@pytest.mark.parametrize("G,L,La,causal", [(1, 2, 2, True), (2, 3, 4, True), (2, 0, 0, False)])
+def test_noise_scale_matches_monte_carlo(G, L, La, causal):
+    """moda_ref_bwd_noise_f64 claims to be the standard deviation (per unit relative rounding
+    error) of the gradient error under its rounding model: draw that model many times on a dense
+    evaluation of the backward and compare the empirical standard deviation."""
+    Hk = 2
+    Q, K, V, Kd, Vd = make(60 + G + L, B=1, Hq=Hk * G, Hk=Hk, T=6, d=4, L=L, La=La)
+    dO = rnd(61, *Q.shape)
+    scale = 0.6
+    exact = _dense_backward(Q, K, V, Kd, Vd, dO, L, causal, scale)
+    ref = R.bwd(Q, K, V, Kd, Vd, dO, depth_count=L, causal=causal, scale=scale)
+    for a, r in zip(exact, ref):
+        if r is not None:
+            np.testing.assert_allclose(a, r, atol=1e-12)
+    noise = R.bwd_noise(Q, K, V, Kd, Vd, dO, depth_count=L, causal=causal, scale=scale)
+    u, draws = 1e-4, 1500
+    rng = np.random.default_rng(7)
+    sq = [None if a is None else np.zeros_like(a) for a in exact]
+    for _ in range(draws):
+        noisy = _dense_backward(Q, K, V, Kd, Vd, dO, L, causal, scale, u=u, rng=rng)
+        for s_, n_, a in zip(sq, noisy, exact):
+            if s_ is not None:
+                s_ += (n_ - a) ** 2
+    for name, s_, n_ in zip(("dQ", "dK", "dV", "dKd", "dVd"), sq, noise):
+        if s_ is None:
+            assert n_ is None
+            continue
+        sd = np.sqrt(s_ / draws) / u
+        # the estimate of a standard deviation from 1500 draws is good to about 2 % (one sigma)
+        np.testing.assert_allclose(sd, n_, rtol=0.12, atol=1e-9, err_msg=name)
+    if La > L:
+        assert not noise[3][:, :, :, L:].any() and not noise[4][:, :, :, L:].any()
+
+
+def test_noise_scale_single_token_closed_form():
+    """T = 1, no depth slots: p = 1 and e = 0, so only the output's rounding is left:
+    nV = |g|, nK = scale D |q|, nQ = scale D |k| with D = sqrt(sum_k (g_k v_k)^2)."""
+    Q, K, V, _, _ = make(70, B=1, Hq=1, Hk=1, T=1, d=5, L=0)
+    dO = rnd(71, *Q.shape)
+    nQ, nK, nV, nKd, nVd = R.bwd_noise(Q, K, V, None, None, dO, scale=0.3)
+    D = math.sqrt(float(((dO * V) ** 2).sum()))
+    np.testing.assert_allclose(nV, np.abs(dO), atol=1e-14)
+    np.testing.assert_allclose(nK, 0.3 * D * np.abs(Q), atol=1e-14)
+    np.testing.assert_allclose(nQ, 0.3 * D * np.abs(K), atol=1e-14)
+    assert nKd is None and nVd is None
+
+
+def test_noise_scale_rows_variant_matches_full():
+    Q, K, V, Kd, Vd = make(72, B=2, Hq=4, Hk=2, T=10, d=4, L=2, La=3)
+    dO = rnd(73, *Q.shape)
+    rows = np.array([0, 9, 4], np.int32)
+    nQ, _, _, nKd, nVd = R.bwd_noise(Q, K, V, Kd, Vd, dO, depth_count=2)
+    rQ, rKd, rVd = R.bwd_noise_rows(Q[:, :, rows], K, V, Kd[:, :, rows], Vd[:, :, rows], dO[:, :, rows], rows,
+                                    depth_count=2)
+    np.testing.assert_allclose(nQ[:, :, rows], rQ, atol=1e-14)
+    np.testing.assert_allclose(nKd[:, :, rows], rKd, atol=1e-14)
+    np.testing.assert_allclose(nVd[:, :, rows], rVd, atol=1e-14)
+
+
 def test_rows_variants_match_full():
     Q, K, V, Kd, Vd = make(40, B=2, Hq=4, Hk=2, T=12, d=4, L=3, La=4)
     dO = rnd(41, *Q.shape)
