@@ -31,6 +31,7 @@ WORKLOADS = {
     "tiny_fp32": (1, 2, 2, 256, 64, 4, "f32"),                 # BASELINE configs[0]
     "bwd_layer_1p5b_4k": (8, 16, 16, 4096, 128, 15, "bf16"),   # BASELINE configs[4] (backward)
     "copy_calibration": None,  # plain device copy of known size, for scaling the HBM byte counters
+    "mfma_calibration": None,  # what the matrix pipe alone sustains (zero and N(0,1) bf16 operands)
     "sweep": None,             # BASELINE configs[3]: B=4 H=16 d=128, T x depth_count grid
     "paper_table2": None,      # the paper's Table 2 shapes (d=64, grouped queries, 64..256 slots), fwd+bwd
     "decode": None,            # one new token per sequence against a 64K sequence cache
@@ -48,6 +49,12 @@ def bwd_flops(B, H, T, d, L, causal=True):
     """10*d per visible pair: five d-length contractions (S, dP, dV, dQ, dK)."""
     pairs = T * (T + 1) // 2 if causal else T * T
     return 10.0 * d * B * H * (pairs + T * L)
+
+
+def bwd_workspace_bytes(B, Hq, Hk, T, d, L):
+    from paper_2603_15619_amd import MODAShape, moda_attn_bwd_workspace_bytes
+
+    return max(16, moda_attn_bwd_workspace_bytes(MODAShape(B, Hq, Hk, T, d, L, L, 1, 0.0, 1)))
 
 
 def measured_traffic(workload, kernel):
@@ -72,6 +79,50 @@ def run_copy_calibration(args):
                       "steps": args.steps, "warmup": args.warmup}))
 
 
+def mfma_calibration(reps=6, target_ms=40.0):
+    """TFLOP/s that a loop of nothing but v_mfma_f32_32x32x16_bf16 sustains on this chip (the
+    library's calibration kernel: 8 waves per workgroup, 4 workgroups per compute unit's worth of
+    grid), on all-zero operands and on N(0,1) operands.  Each figure is the mean of the last
+    `reps - 2` of `reps` launches of about `target_ms` each (the clock settles during the first)."""
+    from paper_2603_15619_amd import lib, moda_calibrate_mfma
+
+    n = int(lib().moda_calibrate_mfma_operand_bytes()) // 2
+    wgs = 256 * 4
+    sink = torch.empty(int(lib().moda_calibrate_mfma_sink_bytes(wgs)) // 4, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    out = {}
+    for name, ops in (("zeros", torch.zeros(n, dtype=torch.bfloat16, device="cuda")),
+                      ("normal", torch.randn(n, generator=gen, device="cuda").to(torch.bfloat16))):
+        iters = 20000
+        for _ in range(2):  # size the launch: about target_ms at the rate just seen
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fl = moda_calibrate_mfma(ops, wgs, iters, sink)
+            b.record()
+            torch.cuda.synchronize()
+            iters = max(1000, int(iters * target_ms / max(a.elapsed_time(b), 1e-3)))
+        rates = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fl = moda_calibrate_mfma(ops, wgs, iters, sink)
+            b.record()
+            torch.cuda.synchronize()
+            rates.append(fl / (a.elapsed_time(b) * 1e-3) / 1e12)
+        out[name] = round(float(np.mean(rates[2:])), 1)
+        out[name + "_launch_ms"] = round(fl / (out[name] * 1e12) * 1e3, 2)
+    return out
+
+
+def run_mfma_calibration(args):
+    cal = mfma_calibration(reps=max(4, args.steps))
+    print(json.dumps({"metric": "bf16 MFMA-only loop (moda_calibrate_mfma_kernel), TFLOP/s", "unit": "TFLOP/s",
+                      "published_peak": PEAK_TFLOPS["bf16"], "operands_zero": cal["zeros"],
+                      "operands_normal": cal["normal"], "launch_ms": [cal["zeros_launch_ms"], cal["normal_launch_ms"]],
+                      "steps": args.steps}))
+
+
 def run_sweep(args):
     """BASELINE configs[3]: TFLOP/s and depth-segment GB/s per (T, depth_count) point."""
     from paper_2603_15619_amd import moda_attn_fwd, synth
@@ -91,12 +142,15 @@ def run_sweep(args):
             if L == 0:
                 t0 = ms
             depth_bytes = 2.0 * B * H * T * L * d * 2
+            alg_bytes = 2.0 * (4 * B * H * T * d) + depth_bytes + 4.0 * B * H * T
+            floor_ms = max(fwd_flops(B, H, T, d, L) / (PEAK_TFLOPS["bf16"] * 1e12), alg_bytes / 8.0e12) * 1e3
             points.append({"T": T, "depth_count": L, "ms": round(ms, 4),
                            "tflops": round(fwd_flops(B, H, T, d, L) / (ms * 1e-3) / 1e12, 1),
                            "ratio_to_depth0": round(t0 / ms, 4),
-                           "depth_gbps_over_extra_time": round(depth_bytes / ((ms - t0) * 1e-3) / 1e9, 1)
-                           if L and ms > t0 else None,
-                           "depth_gbps_over_call": round(depth_bytes / (ms * 1e-3) / 1e9, 1)})
+                           "extra_ms": round(ms - t0, 4),
+                           "depth_gbps_over_call": round(depth_bytes / (ms * 1e-3) / 1e9, 1),
+                           "hbm_frac_over_call": round(alg_bytes / (ms * 1e-3) / 8.0e12, 4),
+                           "roof_ms": round(floor_ms, 4), "frac_of_roof": round(floor_ms / ms, 4)})
     print(json.dumps({"metric": "MoDA attn fwd sweep (B=4 H=16 d=128 bf16 causal)", "steps": args.steps,
                       "warmup": args.warmup, "points": points}))
 
@@ -126,7 +180,7 @@ def run_paper_table2(args):
         inp = synth.make_inputs(1, Hq, Hk, T, 64, L, dtype="bf16", seed=5, device="cuda", with_dO=True)
         O = torch.empty_like(inp["Q"])
         LSE = torch.empty((1, Hq, T), dtype=torch.float32, device="cuda")
-        ws = torch.empty(8 * Hq * T + 256, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(bwd_workspace_bytes(1, Hq, Hk, T, 64, L), dtype=torch.uint8, device="cuda")
         with_bwd = G <= 64
         out = {"row": no, "T": T, "G": G, "Hq": Hq, "Hk": Hk, "depth_count": L, "backward_included": with_bwd,
                "paper_a100_ms": {"fa2": p_fa, "moda": p_moda, "extra_pct": round(100 * (p_moda - p_fa) / p_moda, 2)}}
@@ -203,7 +257,7 @@ def run_backward(args, B, Hq, Hk, T, d, L, dtype):
 
     inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=4, device="cuda", with_dO=True)
     O, LSE = moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], depth_count=L)
-    ws = torch.empty(8 * B * Hq * T + 256, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(bwd_workspace_bytes(B, Hq, Hk, T, d, L), dtype=torch.uint8, device="cuda")
 
     def run():
         moda_attn_bwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"], O, LSE, inp["dO"],
@@ -223,7 +277,9 @@ def run_backward(args, B, Hq, Hk, T, d, L, dtype):
                                (args.workload, B, Hq, T, d, L)},
         "roofline": {"bound": "hbm", "achieved": round(alg_bytes / (ms_kernel * 1e-3) / 1e9, 1), "peak": 8000.0,
                      "unit": "GB/s", "frac": round(alg_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0, 4),
-                     "traffic": measured_traffic(args.workload, "bwd"), "call_ms_mean": round(ms_kernel, 4),
+                     "traffic": measured_traffic(args.workload, "bwd"),
+                     "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc runs), not measured by this run",
+                     "call_ms_mean": round(ms_kernel, 4),
                      "bytes_per_call": alg_bytes, "flops_per_call": flops}}))
 
 
@@ -278,6 +334,7 @@ def main():
     ap.add_argument("--depth-count", type=int, default=None, help="override the workload's depth_count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fa", action="store_true", help="skip the depth_count=0 comparison run")
+    ap.add_argument("--no-calibration", action="store_true", help="skip the MFMA-only calibration loop")
     ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--rows", type=int, nargs="*", default=None, help="paper_table2: only these row numbers")
     args = ap.parse_args()
@@ -293,6 +350,8 @@ def main():
 
     if args.workload == "copy_calibration":
         return run_copy_calibration(args)
+    if args.workload == "mfma_calibration":
+        return run_mfma_calibration(args)
     if args.workload == "sweep":
         return run_sweep(args)
     if args.workload == "paper_table2":
@@ -317,17 +376,26 @@ def main():
     def run_fa():
         moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], None, None, depth_count=0, out=O, lse=LSE)
 
-    fa = None
-    if not args.no_fa and L > 0:
-        fa = time_calls(run_fa, args.steps, args.warmup)
     ms_step, ms_kernel, ms_min = time_calls(run_moda, args.steps, args.warmup)
-    if fa is not None:  # second pass of both, interleaved order, keep the better mean of each
-        fa2 = time_calls(run_fa, args.steps, 1)
-        m2 = time_calls(run_moda, args.steps, 1)
-        if fa2[0] < fa[0]:
-            fa = fa2
-        if m2[0] < ms_step:
-            ms_step, ms_kernel, ms_min = m2
+    # The depth_count = 0 kernel next to it, as interleaved pairs (FA, MoDA, FA, MoDA, ...): each pair
+    # gives one ratio t(depth 0) / t(depth L) at the same clock and cache state; the median of the
+    # pairs is reported with its spread.
+    pairs = None
+    if not args.no_fa and L > 0:
+        run_fa()
+        run_moda()
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(args.steps):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            run_fa()
+            e[1].record()
+            run_moda()
+            e[2].record()
+            evs.append(e)
+        torch.cuda.synchronize()
+        pairs = [(e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])) for e in evs]
 
     flops = fwd_flops(B, Hq, T, d, L)
     value = flops / (ms_step * 1e-3) / 1e12
@@ -338,6 +406,8 @@ def main():
     # fp32, vector) peak against the time its algorithmic bytes need at the HBM peak.
     alg_bytes = esz * (B * T * d * (2 * Hq + 2 * Hk) + 2.0 * B * Hk * T * L * d) + 4.0 * B * Hq * T
     common = {"traffic": measured_traffic(args.workload, "fwd"),
+              "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                "command), not measured by this run",
               "kernel": ("moda_fwd_bf16_kernel<%d, 8>" % d) if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
               "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
               "flops_per_launch": flops, "bytes_per_launch": alg_bytes}
@@ -358,15 +428,25 @@ def main():
                                (args.workload, B, Hq, Hk, T, d, L)},
         "roofline": roofline,
     }
-    if fa is not None:
+    if pairs is not None:
+        fa_ms = float(np.median([a for a, _ in pairs]))
+        moda_ms = float(np.median([b for _, b in pairs]))
+        ratios = sorted(a / b for a, b in pairs)
         fa_flops = fwd_flops(B, Hq, T, d, 0)
-        out["ratio_to_causal_fa"] = round(fa[0] / ms_step, 4)
-        out["causal_fa"] = {"ms_per_step": round(fa[0], 4),
-                            "tflops": round(fa_flops / (fa[0] * 1e-3) / 1e12, 2)}
-        extra = (ms_step - fa[0]) * 1e-3
-        out["depth_segment"] = {"bytes": depth_bytes, "extra_ms": round(ms_step - fa[0], 4),
-                                "gbps_over_extra_time": round(depth_bytes / extra / 1e9, 1) if extra > 0 else None,
+        out["ratio_to_causal_fa"] = round(float(np.median(ratios)), 4)
+        out["ratio_to_causal_fa_spread"] = {"min": round(ratios[0], 4), "max": round(ratios[-1], 4),
+                                            "pairs": len(ratios), "formed": "median over interleaved (FA, MoDA) pairs"}
+        out["causal_fa"] = {"ms_median": round(fa_ms, 4), "tflops": round(fa_flops / (fa_ms * 1e-3) / 1e12, 2)}
+        # the depth slots' bytes against the whole call (part of the stream overlaps with other
+        # workgroups' key loops, so bytes / extra time is not a bandwidth and is not reported)
+        out["depth_segment"] = {"bytes": depth_bytes, "extra_ms_median": round(moda_ms - fa_ms, 4),
                                 "gbps_over_whole_call": round(depth_bytes / (ms_step * 1e-3) / 1e9, 1)}
+    if dtype == "bf16" and not args.no_calibration:
+        cal = mfma_calibration()
+        roofline["peak_measured"] = {"mfma_loop_zero_operands": cal["zeros"], "mfma_loop_normal_operands": cal["normal"],
+                                     "unit": "TFLOP/s", "kernel": "moda_calibrate_mfma_kernel, this run"}
+        if roofline["bound"] == "mfma":
+            roofline["frac_of_measured"] = round(achieved / cal["normal"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, T, d, L, Hq, args.cpu_rows)
     print(json.dumps(out))

@@ -4,11 +4,17 @@
  * C ABI.  Every data pointer is a DEVICE pointer owned by the caller; the
  * shape struct and the return values live on the host.  The library never
  * allocates, frees or keeps a pointer; its only scratch is the workspace the
- * caller passes to the backward call.  Calls are asynchronous on the given HIP
- * stream (NULL = the default stream), never synchronise the device, and hold
- * no global mutable state.  Errors are reported by return code only: on any
- * status other than MODA_OK no kernel has been launched and no output has
- * been touched.
+ * caller passes to the backward and decoding calls.  Calls are asynchronous on
+ * the given HIP stream (NULL = the default stream), never synchronise the
+ * device, read no environment variable and hold no global mutable state.
+ * Errors are reported by return code only.  Every argument check (pointers,
+ * shapes, alignment, workspace size, the size of every kernel grid) is made
+ * before the first kernel is enqueued: on any status other than MODA_OK and
+ * MODA_ERR_LAUNCH nothing has been launched and no output has been touched.
+ * MODA_ERR_LAUNCH means the HIP runtime refused a kernel launch of this call
+ * (the code is that launch's own return value, not an error left behind by
+ * earlier work of the caller); kernels of the same call that were enqueued
+ * before it still run, so the outputs are then unspecified.
  *
  * The operator (paper section 2.2 "Mixture-of-Depths Attention"; Eq. 2 for the
  * sequence part; Algorithm 1 for the index sets and the shared online-softmax
@@ -69,8 +75,15 @@ typedef struct {
   int32_t depth_count; /* slots [0, depth_count) are attended; <= depth_alloc             */
   int32_t causal;      /* 1: sequence keys j <= t (Eq. 2's causal mask); 0: all T keys    */
   float scale;         /* softmax scale; <= 0 selects Eq. 2's 1/sqrt(d)                   */
-  int32_t dtype;       /* a moda_dtype: type of Q, K, V, depth tensors, O, dO, gradients  */
+  moda_dtype dtype;    /* type of Q, K, V, depth tensors, O, dO, gradients (a 32-bit enum) */
 } moda_shape;
+
+/*
+ * Size limits of this build (MODA_ERR_UNSUPPORTED beyond them): d is 64 or 128; one
+ * (batch, head) slab of a SEQUENCE tensor, T * d elements, stays below 4 GiB (32-bit byte
+ * offsets inside a slab); depth_alloc <= 8192.  The depth tensors themselves are addressed
+ * with 64-bit tile bases and may be of any size.
+ */
 
 /*
  * Forward pass of the operator defined above (Algorithm 1: sequence blocks,
@@ -84,6 +97,26 @@ typedef struct {
 moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
                           const void* Vdepth, void* O, float* LSE, const moda_shape* s,
                           void* hip_stream);
+
+/*
+ * The same forward pass with the launch geometry of the bf16 kernel chosen by the caller
+ * instead of derived from the shape (for experiments and for tests that must reach every
+ * code path; the result is the same operator whatever the geometry).  A field that is 0
+ * keeps the library's own choice; `tuning` == NULL is moda_attn_fwd.
+ *   waves           4 or 8: waves (of 32 queries each) per workgroup
+ *   heads_per_tile  query heads of one group that share a tile; divides both Hq / Hk and
+ *                   `waves`
+ *   head_group      (batch, head) units that one die walks together, tile by tile; >= 1
+ * Values that the kernel cannot run are rejected with MODA_ERR_SHAPE.  Ignored for fp32.
+ */
+typedef struct {
+  int32_t waves;
+  int32_t heads_per_tile;
+  int32_t head_group;
+} moda_fwd_tuning;
+moda_status moda_attn_fwd_tuned(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                                const void* Vdepth, void* O, float* LSE, const moda_shape* s,
+                                const moda_fwd_tuning* tuning, void* hip_stream);
 
 /*
  * Backward pass.  The paper times it (Table 2, "forward&backward") but gives
@@ -144,6 +177,24 @@ moda_status moda_attn_decode(const void* Q, const void* Kseq, const void* Vseq, 
                              const void* Vdepth, void* O, float* LSE, int32_t kv_alloc, void* workspace,
                              size_t workspace_bytes, const moda_shape* s, void* hip_stream);
 
+/*
+ * Measurement aid: a kernel whose loop holds nothing but the bf16 matrix instruction the
+ * attention kernels use (v_mfma_f32_32x32x16_bf16; eight waves per workgroup, four independent
+ * accumulators per wave), for reporting what the matrix pipe of THIS chip sustains next to its
+ * published peak.  The operands are read once from `operands`
+ * (moda_calibrate_mfma_operand_bytes() bytes of bf16, device, 16-byte aligned): the sustained
+ * rate depends on their values (the clock follows the power they draw), so the caller passes
+ * zeros, or values distributed like its workload's.  `sink` (device,
+ * moda_calibrate_mfma_sink_bytes(workgroups) bytes) receives one float per thread.  Enqueues
+ * one launch of `workgroups` workgroups x `iters` loop passes on `hip_stream` and returns the
+ * floating-point operations it performs (0 if an argument is bad or the launch is refused);
+ * the caller times it with HIP events.
+ */
+size_t moda_calibrate_mfma_operand_bytes(void);
+size_t moda_calibrate_mfma_sink_bytes(int32_t workgroups);
+double moda_calibrate_mfma(const void* operands, float* sink, size_t sink_bytes, int32_t workgroups, int32_t iters,
+                           void* hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* moda_status_string(moda_status st);
 
@@ -151,10 +202,8 @@ const char* moda_status_string(moda_status st);
 int moda_version(void);
 
 /*
- * Time of the most recent forward (which = 0) or backward (which = 1) launch
- * sequence of this thread is NOT tracked by the library; callers time with HIP
- * events on their own stream.  This helper only reports how many kernels one
- * call of the given kind launches for shape `s` (0 for an empty problem), so a
+ * Number of kernels that one forward (which = 0) or backward (which = 1) call
+ * enqueues for shape `s` (0 for an empty or unsupported problem), so that a
  * profiler's per-kernel rows can be matched to calls.
  */
 int moda_kernels_per_call(const moda_shape* s, int which);

@@ -14,8 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MODA_LIB_PATH") or os.path.join(HERE, "libmoda.so")
 
 MODA_F32, MODA_BF16 = 0, 1
-EXPORTS = ("moda_attn_fwd", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd", "moda_depth_append",
+EXPORTS = ("moda_attn_fwd", "moda_attn_fwd_tuned", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd", "moda_depth_append",
            "moda_attn_decode", "moda_attn_decode_workspace_bytes",
+           "moda_calibrate_mfma", "moda_calibrate_mfma_operand_bytes", "moda_calibrate_mfma_sink_bytes",
            "moda_status_string", "moda_version", "moda_kernels_per_call")
 
 
@@ -24,6 +25,10 @@ class MODAShape(ctypes.Structure):
                 ("T", ctypes.c_int32), ("d", ctypes.c_int32), ("depth_alloc", ctypes.c_int32),
                 ("depth_count", ctypes.c_int32), ("causal", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+
+
+class MODAFwdTuning(ctypes.Structure):
+    _fields_ = [("waves", ctypes.c_int32), ("heads_per_tile", ctypes.c_int32), ("head_group", ctypes.c_int32)]
 
 
 class MODAError(RuntimeError):
@@ -47,6 +52,8 @@ def lib():
         sp = ctypes.POINTER(MODAShape)
         L.moda_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, vp]
         L.moda_attn_fwd.restype = ctypes.c_int
+        L.moda_attn_fwd_tuned.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, ctypes.POINTER(MODAFwdTuning), vp]
+        L.moda_attn_fwd_tuned.restype = ctypes.c_int
         L.moda_attn_bwd_workspace_bytes.argtypes = [sp]
         L.moda_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.moda_attn_bwd.argtypes = [vp] * 14 + [ctypes.c_size_t, sp, vp]
@@ -57,6 +64,12 @@ def lib():
         L.moda_attn_decode_workspace_bytes.restype = ctypes.c_size_t
         L.moda_attn_decode.argtypes = [vp] * 7 + [ctypes.c_int32, vp, ctypes.c_size_t, sp, vp]
         L.moda_attn_decode.restype = ctypes.c_int
+        L.moda_calibrate_mfma_operand_bytes.argtypes = []
+        L.moda_calibrate_mfma_operand_bytes.restype = ctypes.c_size_t
+        L.moda_calibrate_mfma_sink_bytes.argtypes = [ctypes.c_int32]
+        L.moda_calibrate_mfma_sink_bytes.restype = ctypes.c_size_t
+        L.moda_calibrate_mfma.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp]
+        L.moda_calibrate_mfma.restype = ctypes.c_double
         L.moda_status_string.argtypes = [ctypes.c_int]
         L.moda_status_string.restype = ctypes.c_char_p
         L.moda_version.restype = ctypes.c_int
@@ -115,11 +128,13 @@ def _stream(device):
 
 
 def moda_attn_fwd(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, depth_count=None, causal=True,
-                  scale=None, out=None, lse=None):
+                  scale=None, out=None, lse=None, tuning=None):
     """O, LSE = MoDA attention forward on the current stream of Q's device.
 
     Q [B,Hq,T,d]; Kseq/Vseq [B,Hk,T,d]; Kdepth/Vdepth [B,Hk,T,depth_alloc,d] or
     None; slots [0, depth_count) of each position are attended (default: all).
+    `tuning` = dict(waves=, heads_per_tile=, head_group=) calls moda_attn_fwd_tuned (the bf16
+    kernel's launch geometry chosen by the caller; missing keys keep the library's choice).
     """
     s = make_shape(Q, Kseq, Kdepth, depth_count, causal, scale)
     dev, dt = Q.device, Q.dtype
@@ -135,8 +150,14 @@ def moda_attn_fwd(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, depth_count=None, cau
     _require(out, "out", Q.shape, dt, dev)
     _require(lse, "lse", (s.B, s.Hq, s.T), torch.float32, dev)
     with torch.cuda.device(dev):
-        _check(lib().moda_attn_fwd(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth),
-                                   _ptr(out), _ptr(lse), ctypes.byref(s), _stream(dev)))
+        if tuning is None:
+            _check(lib().moda_attn_fwd(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth),
+                                       _ptr(out), _ptr(lse), ctypes.byref(s), _stream(dev)))
+        else:
+            tn = MODAFwdTuning(int(tuning.get("waves", 0)), int(tuning.get("heads_per_tile", 0)),
+                               int(tuning.get("head_group", 0)))
+            _check(lib().moda_attn_fwd_tuned(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth),
+                                             _ptr(out), _ptr(lse), ctypes.byref(s), ctypes.byref(tn), _stream(dev)))
     return out, lse
 
 
@@ -225,3 +246,21 @@ def moda_attn_decode(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, T=None, depth_coun
                                       _ptr(lse), int(kv_alloc), _ptr(workspace), ws_bytes, ctypes.byref(s),
                                       _stream(dev)))
     return out, lse
+
+
+def moda_calibrate_mfma(operands, workgroups, iters, sink=None):
+    """Enqueue the matrix-pipe calibration kernel on the current stream; returns the floating-point
+    operations of the launch.  `operands`: bf16 tensor of moda_calibrate_mfma_operand_bytes() bytes."""
+    dev = operands.device
+    need = int(lib().moda_calibrate_mfma_operand_bytes())
+    if operands.dtype != torch.bfloat16 or operands.numel() * 2 < need or not operands.is_contiguous():
+        raise ValueError("operands: contiguous bf16 tensor of at least %d bytes" % need)
+    sb = int(lib().moda_calibrate_mfma_sink_bytes(int(workgroups)))
+    if sink is None:
+        sink = torch.empty(sb // 4, dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        fl = float(lib().moda_calibrate_mfma(_ptr(operands), _ptr(sink), sink.numel() * 4, int(workgroups), int(iters),
+                                             _stream(dev)))
+    if fl <= 0:
+        raise MODAError(5, "calibration launch rejected")
+    return fl

@@ -14,15 +14,17 @@
 //            pipe, P and dS = P (dP - delta) are packed to bf16 straight out of the
 //            accumulators and contracted over the queries into dV^T, dK^T.  The same
 //            workgroup also takes the depth slots of its 128 positions (row-local: dKdepth,
-//            dVdepth and the depth share of dQ, left in the dQ buffer), before or after its
-//            key-tile work: that part is bound by HBM, the rest by the matrix pipe.
+//            dVdepth and the depth share of dQ, left in the workspace in fp32), before or
+//            after its key-tile work: that part is bound by HBM, the rest by the matrix pipe.
 //   dq     : one workgroup per 128 queries; K / V tiles stream through LDS; S^T, dP^T
 //            are recomputed in the transposed orientation (a lane owns one query),
-//            dQ^T += K^T dS^T on top of the depth share found in the dQ buffer.
+//            dQ^T += K^T dS^T on top of the depth share found in the workspace; every
+//            element of dQ is rounded to bf16 once.
 // Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 64): the
 // gradients of the shared keys and values sum over the group.  dkdv walks the query
 // tiles of all G heads; the depth-slot gradients are computed by a kernel of their own
-// (depth_gqa) that holds the G heads of a position side by side.
+// (depth_gqa for G <= 8, depth_gqa_wide above) that holds the G heads of a position side by
+// side, sums in fp32 and rounds every depth gradient once.
 #include <type_traits>
 
 #include "moda_launch.h"
@@ -71,8 +73,8 @@ __device__ __forceinline__ bf16x8 pack8(const float (&x)[8]) {
 // ---------------------------------------------------------------- depth-slot gradients (G = 1)
 // The depth slots of 32 consecutive positions (row0 ...) of one head, handled by one wave in a
 // row-major mapping (d/8 lanes x 8 channels per row, 64 / (d/8) rows per wave step): dKdepth,
-// dVdepth (row-local, written once) and the depth share of dQ, which is left in the dQ buffer
-// (not yet multiplied by the softmax scale, rounded to bf16) for the dQ kernel to start from.
+// dVdepth (row-local, written once) and the depth share of dQ, which is left in the workspace
+// (fp32, not yet multiplied by the softmax scale) for the dQ kernel to start from.
 // Work items (row step, chunk of kChunk slots) are walked with the loads of the next two
 // items in flight (the phase is bound by memory latency).  Uses no LDS.
 template <int D>
@@ -88,14 +90,19 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
   const float* statb = p.rowstat + (size_t)bh * T * 2;
   const int rg = lane / LPR, l16 = lane % LPR;
   const size_t drow = (size_t)La * Tl::kRowBytes;
-  const size_t slab = (size_t)T * drow;
   // (this phase only runs when every key/value head serves one query head: bg == bh)
-  const char* Kdb = (const char*)p.Kdepth + (size_t)bg * slab;
-  const char* Vdb = (const char*)p.Vdepth + (size_t)bg * slab;
-  char* dKdb = (char*)p.dKdepth + (size_t)bg * slab;
-  char* dVdb = (char*)p.dVdepth + (size_t)bg * slab;
-  char* dQb = (char*)p.dQ + (size_t)bh * T * Tl::kRowBytes;
-  // raw buffers with 32-bit offsets
+  // The depth tensors are addressed from the first of the wave's 32 positions (a 64-bit base)
+  // with 32-bit offsets from there, so they may be of any size; `slab` is what is left of the
+  // (batch, head) slab from that position on, clamped to what 32 bits hold.
+  const int rbase = min(qw0, T - 1);
+  const size_t dbase = ((size_t)bg * T + rbase) * drow;
+  const size_t left = (size_t)(T - rbase) * drow;
+  const size_t slab = left < 0xffffffffull ? left : 0xffffffffull;
+  const char* Kdb = (const char*)p.Kdepth + dbase;
+  const char* Vdb = (const char*)p.Vdepth + dbase;
+  char* dKdb = (char*)p.dKdepth + dbase;
+  char* dVdb = (char*)p.dVdepth + dbase;
+  float* dQd = p.dq_depth + (size_t)bh * T * D;
   const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Kdb, 0, (int)(unsigned)slab, 0x00020000);
   const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)Vdb, 0, (int)(unsigned)slab, 0x00020000);
   const __amdgpu_buffer_rsrc_t dkd_buf = __builtin_amdgcn_make_buffer_rsrc((void*)dKdb, 0, (int)(unsigned)slab, 0x00020000);
@@ -115,9 +122,9 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
   auto end_row = [&](int row) {
     const int t = qw0 + row;
     if (t < T) {
-      u32x4 ov = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
-                  pack_bf16(acc[6], acc[7])};
-      *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
+      float* dst = dQd + (size_t)t * D + l16 * 8;
+      *(f32x4*)dst = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+      *(f32x4*)(dst + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
     }
   };
   if (L == 0) {  // no attended slots: a zero share of dQ, zero gradients for allocated slots
@@ -128,8 +135,8 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
       if (t < T) {
         const u32x4 z = {0u, 0u, 0u, 0u};
         for (int i = 0; i < La; ++i) {
-          *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-          *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dVdb + (size_t)(t - rbase) * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dKdb + (size_t)(t - rbase) * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
         }
       }
     }
@@ -142,7 +149,7 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
     const f32x2 st = *(const f32x2*)(statb + 2 * tc);
     b.l2 = st[0];
     b.dl = st[1];
-    const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+    const int voff = (int)((unsigned)(tc - rbase) * (unsigned)drow + (unsigned)l16 * 16u);  // 32 positions' slots: far below 4 GiB
     // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
@@ -154,7 +161,7 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
   auto fold = [&](int it, int c, const Item& b) {
     const int t = qw0 + it * RPS + rg;
     const bool live = t < T;  // rows past the end compute on row T-1 and store nothing
-    const int voff = (int)((unsigned)min(t, T - 1) * (unsigned)drow + (unsigned)l16 * 16u);
+    const int voff = (int)((unsigned)(min(t, T - 1) - rbase) * (unsigned)drow + (unsigned)l16 * 16u);
     const int soff = c * kChunk * Tl::kRowBytes;
     float qx[8], gx[8];
 #pragma unroll
@@ -233,8 +240,8 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
       if (t < T) {
         const u32x4 z = {0u, 0u, 0u, 0u};
         for (int i = nch * kChunk; i < La; ++i) {
-          *(u32x4*)(dVdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
-          *(u32x4*)(dKdb + (size_t)t * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dVdb + (size_t)(t - rbase) * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
+          *(u32x4*)(dKdb + (size_t)(t - rbase) * drow + (size_t)i * Tl::kRowBytes + l16 * 16) = z;
         }
       }
     }
@@ -497,18 +504,18 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
   const int La = p.depth_alloc;
 
   // The depth-slot gradients and the depth share of dQ were computed before this kernel (by
-  // the dK/dV kernel, or by moda_bwd_depth_gqa_kernel with grouped queries); the share is in
-  // the dQ buffer, not yet multiplied by the softmax scale, rounded to bf16.
+  // the dK/dV kernel, or by the depth_gqa kernels with grouped queries); the share is in the
+  // workspace, in fp32, not yet multiplied by the softmax scale.
   f32x16 dq[Tl::kDBlocks];
   if (La > 0) {
-    const char* src = (const char*)p.dQ + ((size_t)bh * T + qrow) * Tl::kRowBytes;
+    const float* src = p.dq_depth + ((size_t)bh * T + qrow) * D;
 #pragma unroll
     for (int db = 0; db < Tl::kDBlocks; ++db)
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
-        const u32x2 v = *(const u32x2*)(src + (db * 32 + bq * 8 + hi * 4) * 2);
-        dq[db][4 * bq] = bf16_lo(v[0]); dq[db][4 * bq + 1] = bf16_hi(v[0]);
-        dq[db][4 * bq + 2] = bf16_lo(v[1]); dq[db][4 * bq + 3] = bf16_hi(v[1]);
+        const f32x4 v = *(const f32x4*)(src + db * 32 + bq * 8 + hi * 4);
+        dq[db][4 * bq] = v[0]; dq[db][4 * bq + 1] = v[1];
+        dq[db][4 * bq + 2] = v[2]; dq[db][4 * bq + 3] = v[3];
       }
   } else {
 #pragma unroll
@@ -631,15 +638,13 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
 
 // ---------------------------------------------------------------- depth-slot gradients, grouped queries
 // One row = one (batch, key/value head, position); d/8 lanes x 8 channels per row.  The GT
-// (>= G) query heads of the group are resident (their Q and dO rows, LSE, delta, and their
-// depth share of dQ); the row's slots stream by, one prefetched ahead.  Per slot i:
-//   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (one rounding each),
-//   dQ_h     += e_{h,i} k_i          (left in the dQ buffer, unscaled, for the dQ kernel).
-// Groups of more than GT = 8 heads take one launch per 8 heads (`head0` = first head of the
-// launch within its group); every launch after the first adds to the dKdepth / dVdepth the
-// previous ones wrote (read, add in fp32, round again).
+// (>= G, G <= 8) query heads of the group are resident (their Q and dO rows, LSE, delta, and
+// their depth share of dQ); the row's slots stream by, one prefetched ahead.  Per slot i:
+//   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (summed in fp32, one
+//                                    rounding each),
+//   dQ_h     += e_{h,i} k_i          (left in the workspace, fp32, unscaled, for the dQ kernel).
 template <int D, int GT>
-__global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p, int head0) {
+__global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p) {
   constexpr int LPR = D / 8, ROWS = 256 / LPR, RB = D * 2;
   const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
   const int tid = threadIdx.x, l16 = tid % LPR;
@@ -656,7 +661,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p,
   float l2[GT], dl[GT], dq[GT][8];
 #pragma unroll
   for (int j = 0; j < GT; ++j) {
-    const int bh = bh0 + min(head0 + j, G - 1);  // heads past the group repeat the last one with weight zero
+    const int bh = bh0 + min(j, G - 1);  // heads past the group repeat the last one with weight zero
     q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
     g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
     const f32x2 st = *(const f32x2*)(p.rowstat + ((size_t)bh * T + t) * 2);
@@ -699,7 +704,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p,
       }
       sdot = group_sum<LPR>(sdot);
       gdot = group_sum<LPR>(gdot);
-      const float pe = head0 + j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
+      const float pe = j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
       const float e = pe * (gdot - dl[j]);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -713,16 +718,6 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p,
     }
     if (live) {
       const float f = p.scale;
-      if (head0 > 0) {  // add what the launches for the heads before wrote (already scaled)
-        const u32x4 pv = *(const u32x4*)(dvd + (size_t)i * RB), pk = *(const u32x4*)(dkd + (size_t)i * RB);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          av[2 * k] += bf16_lo(pv[k]);
-          av[2 * k + 1] += bf16_hi(pv[k]);
-          ak[2 * k] += bf16_lo(pk[k]) / f;
-          ak[2 * k + 1] += bf16_hi(pk[k]) / f;
-        }
-      }
       const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
       const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
                         pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
@@ -732,27 +727,173 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p,
   }
   if (live) {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = L; i < La && head0 == 0; ++i) {  // allocated but unattended slots get zero gradients
+    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
       *(u32x4*)(dvd + (size_t)i * RB) = z;
       *(u32x4*)(dkd + (size_t)i * RB) = z;
     }
 #pragma unroll
     for (int j = 0; j < GT; ++j)
-      if (head0 + j < G) {
-        const u32x4 ov = {pack_bf16(dq[j][0], dq[j][1]), pack_bf16(dq[j][2], dq[j][3]),
-                          pack_bf16(dq[j][4], dq[j][5]), pack_bf16(dq[j][6], dq[j][7])};
-        *(u32x4*)((char*)p.dQ + ((size_t)(bh0 + head0 + j) * T + t) * RB + l16 * 16) = ov;
+      if (j < G) {
+        float* dst = p.dq_depth + ((size_t)(bh0 + j) * T + t) * D + l16 * 8;
+        *(f32x4*)dst = (f32x4){dq[j][0], dq[j][1], dq[j][2], dq[j][3]};
+        *(f32x4*)(dst + 4) = (f32x4){dq[j][4], dq[j][5], dq[j][6], dq[j][7]};
       }
   }
 }
 
+// Sum over the lanes that differ from this one in the lane-index bits >= log2(FROM) (FROM = 8
+// or 16): lane l, l ^ FROM, l ^ 2 FROM, ..., i.e. over the 64 / FROM lanes with equal l % FROM.
+template <int FROM>
+__device__ __forceinline__ float sum_across_groups(float x) {
+  if (FROM == 8) x += dpp_mov<0x128>(x);  // row_ror:8 inside a row of 16 lanes = lane ^ 8
+  {                                       // lane ^ 16: the two rows of each half swap
+    const int xi = __builtin_bit_cast(int, x);
+    auto r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    x = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
+  }
+  return pair_sum(x);                     // lane ^ 32
+}
+
+// Groups of more than 8 query heads (8 < G <= 64).  One WAVE = one (batch, key/value head,
+// position); lane = (head within a set of HS = 64 / (d/8) heads, 8 channels): the heads of a set
+// work side by side, NS = ceil(G / HS) sets one after the other.  Per slot the lanes of a head
+// reduce the two dot products over its channels, the head's contributions to dKdepth_i and
+// dVdepth_i are summed over the sets in registers and over the heads of a set across lanes, in
+// fp32, and rounded once; each head's depth share of dQ stays in registers over the slots and
+// goes to the workspace in fp32.  RESIDENT: the heads' Q / dO rows stay in registers (NS <= 8);
+// otherwise they are re-read (from the caches) for every slot.
+template <int D, int NS, bool RESIDENT>
+__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams p) {
+  constexpr int LPR = D / 8, HS = 64 / LPR, RB = D * 2;
+  const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
+  const int lane = threadIdx.x & 63, l16 = lane % LPR, hs = lane / LPR;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b * Hk + g) * T + t
+  if (row >= (long long)p.B * p.Hk * T) return;  // the whole wave leaves; no workgroup barrier below
+  const int t = (int)(row % T);
+  const int bg = (int)(row / T);
+  const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;
+  const float c2 = p.scale_log2;
+
+  // head of set s on this lane: s * HS + hs (heads past the group repeat the last one, weight zero)
+  auto head_row = [&](int s) { return (size_t)(bh0 + min(s * HS + hs, G - 1)) * T + t; };
+  u32x4 q[RESIDENT ? NS : 1], g[RESIDENT ? NS : 1];
+  float l2[NS], dl[NS], dq[NS][8];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    if (RESIDENT) {
+      q[s] = *(const u32x4*)((const char*)p.Q + head_row(s) * RB + l16 * 16);
+      g[s] = *(const u32x4*)((const char*)p.dO + head_row(s) * RB + l16 * 16);
+    }
+    const f32x2 st = *(const f32x2*)(p.rowstat + head_row(s) * 2);
+    l2[s] = st[0];
+    dl[s] = st[1];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dq[s][k] = 0.f;
+  }
+  const size_t drow = (size_t)La * RB;
+  const char* kd = (const char*)p.Kdepth + (size_t)row * drow + l16 * 16;
+  const char* vd = (const char*)p.Vdepth + (size_t)row * drow + l16 * 16;
+  char* dkd = (char*)p.dKdepth + (size_t)row * drow + l16 * 16;
+  char* dvd = (char*)p.dVdepth + (size_t)row * drow + l16 * 16;
+
+  // two slots in flight ahead of the one being worked on
+  u32x4 kn[2], vn[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    kn[u] = L > 0 ? __builtin_nontemporal_load((const u32x4*)(kd + (size_t)min(u, L - 1) * RB)) : (u32x4){0u, 0u, 0u, 0u};
+    vn[u] = L > 0 ? __builtin_nontemporal_load((const u32x4*)(vd + (size_t)min(u, L - 1) * RB)) : (u32x4){0u, 0u, 0u, 0u};
+  }
+  for (int i = 0; i < L; ++i) {
+    const u32x4 kv = kn[0], vv = vn[0];
+    kn[0] = kn[1];
+    vn[0] = vn[1];
+    const int inext = min(i + 2, L - 1);
+    kn[1] = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
+    vn[1] = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
+    float kx[8], ak[8], av[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      kx[2 * k] = bf16_lo(kv[k]);
+      kx[2 * k + 1] = bf16_hi(kv[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ak[k] = av[k] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      u32x4 qs, gs;
+      if (RESIDENT) {
+        qs = q[s];
+        gs = g[s];
+      } else {
+        qs = *(const u32x4*)((const char*)p.Q + head_row(s) * RB + l16 * 16);
+        gs = *(const u32x4*)((const char*)p.dO + head_row(s) * RB + l16 * 16);
+      }
+      float sdot = 0.f, gdot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        sdot = dot2_bf16(qs[k], kv[k], sdot);
+        gdot = dot2_bf16(gs[k], vv[k], gdot);
+      }
+      sdot = group_sum<LPR>(sdot);
+      gdot = group_sum<LPR>(gdot);
+      const float pe = s * HS + hs < G ? fast_exp2(sdot * c2 - l2[s]) : 0.f;
+      const float e = pe * (gdot - dl[s]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        av[2 * k] += pe * bf16_lo(gs[k]);
+        av[2 * k + 1] += pe * bf16_hi(gs[k]);
+        ak[2 * k] += e * bf16_lo(qs[k]);
+        ak[2 * k + 1] += e * bf16_hi(qs[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dq[s][k] += e * kx[k];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      av[k] = sum_across_groups<LPR>(av[k]);
+      ak[k] = sum_across_groups<LPR>(ak[k]);
+    }
+    if (hs == 0) {
+      const float f = p.scale;
+      const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
+      const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
+                        pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
+      __builtin_nontemporal_store(o1, (u32x4*)(dvd + (size_t)i * RB));
+      __builtin_nontemporal_store(o2, (u32x4*)(dkd + (size_t)i * RB));
+    }
+  }
+  if (hs == 0) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
+      *(u32x4*)(dvd + (size_t)i * RB) = z;
+      *(u32x4*)(dkd + (size_t)i * RB) = z;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    if (s * HS + hs < G) {
+      float* dst = p.dq_depth + head_row(s) * D + l16 * 8;
+      *(f32x4*)dst = (f32x4){dq[s][0], dq[s][1], dq[s][2], dq[s][3]};
+      *(f32x4*)(dst + 4) = (f32x4){dq[s][4], dq[s][5], dq[s][6], dq[s][7]};
+    }
+}
+
 // ---------------------------------------------------------------- launchers
-size_t bwd_bf16_workspace_bytes(const BwdParams& p) { return (size_t)p.B * p.Hq * p.T * 2 * sizeof(float); }
+// Workspace: (LSE log2 e, delta) per query row, then - when there are depth slots - the depth
+// share of dQ in fp32, [B, Hq, T, d].
+static size_t rowstat_bytes(const BwdParams& p) {
+  return (((size_t)p.B * p.Hq * p.T * 2 * sizeof(float)) + 255) / 256 * 256;
+}
+size_t bwd_bf16_workspace_bytes(const BwdParams& p, int d) {
+  return rowstat_bytes(p) + (p.depth_alloc > 0 ? (size_t)p.B * p.Hq * p.T * d * sizeof(float) : 0);
+}
 
 int bwd_bf16_max_group() { return 64; }
 
+int bwd_bf16_kernels(const BwdParams& p) { return 3 + ((p.Hq / p.Hk > 1 && p.depth_alloc > 0) ? 1 : 0); }
+
 template <int D>
-static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
+static hipError_t launch_bwd_bf16_d(BwdParams p, hipStream_t stream) {
   const long long rows = (long long)p.B * p.Hq * p.T;
   const int G = p.Hq / p.Hk;
   const long long g_delta = (rows * (D / 8) + 255) / 256;
@@ -761,23 +902,32 @@ static hipError_t launch_bwd_bf16_d(const BwdParams& p, hipStream_t stream) {
   constexpr int kDqWaves = 4;
   const long long g_dq = (long long)p.B * p.Hq * ((p.T + kDqWaves * 32 - 1) / (kDqWaves * 32));
   const long long kv_rows = (long long)p.B * p.Hk * p.T;
-  const long long g_depth = (kv_rows * (D / 8) + 255) / 256;
-  if (g_delta > 0x7fffffffLL || g_dq > 0x7fffffffLL || g_depth > 0x7fffffffLL) return hipErrorInvalidValue;
+  const long long g_depth = (kv_rows * (D / 8) + 255) / 256;  // G <= 8: 256 / (d/8) positions per workgroup
+  const long long g_wide = (kv_rows + 3) / 4;                  // G > 8: one wave per position
+  // every grid is checked before the first kernel is enqueued
+  if (!grid_ok(g_delta) || !grid_ok(g_dkdv) || !grid_ok(g_dq) || !grid_ok(g_depth) || !grid_ok(g_wide))
+    return kGridTooLarge;
   if (G > bwd_bf16_max_group()) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), 0, stream, p.dO, p.O, p.LSE,
-                     p.rowstat, rows);
+  p.dq_depth = (float*)((char*)p.rowstat + rowstat_bytes(p));
+  hipError_t e = launch_kernel(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), stream, p.dO, p.O, p.LSE,
+                               p.rowstat, rows);
+  if (e != hipSuccess) return e;
   if (G > 1 && p.depth_alloc > 0) {
-    if (G <= 2)
-      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 2>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, 0);
-    else if (G <= 4)
-      hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 4>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, 0);
-    else
-      for (int head0 = 0; head0 < G; head0 += 8)
-        hipLaunchKernelGGL((moda_bwd_depth_gqa_kernel<D, 8>), dim3((unsigned)g_depth), dim3(256), 0, stream, p, head0);
+    const dim3 gd((unsigned)g_depth), gw((unsigned)g_wide), blk(256);
+    constexpr int HS = 64 / (D / 8);  // heads side by side in the wide kernel
+    const int ns = (G + HS - 1) / HS;
+    if (G <= 2) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 2>, gd, blk, stream, p);
+    else if (G <= 4) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 4>, gd, blk, stream, p);
+    else if (G <= 8) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 8>, gd, blk, stream, p);
+    else if (ns <= 2) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 2, true>, gw, blk, stream, p);
+    else if (ns <= 4) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 4, true>, gw, blk, stream, p);
+    else if (ns <= 8) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 8, true>, gw, blk, stream, p);
+    else e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 16, false>, gw, blk, stream, p);
+    if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), 0, stream, p);
-  hipLaunchKernelGGL((moda_bwd_dq_kernel<D, kDqWaves>), dim3((unsigned)g_dq), dim3(kDqWaves * 64), 0, stream, p);
-  return hipGetLastError();
+  e = launch_kernel(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), stream, p);
+  if (e != hipSuccess) return e;
+  return launch_kernel(moda_bwd_dq_kernel<D, kDqWaves>, dim3((unsigned)g_dq), dim3(kDqWaves * 64), stream, p);
 }
 
 hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream) {

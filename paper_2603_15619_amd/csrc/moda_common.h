@@ -36,7 +36,7 @@ struct FwdParams {
   int head_group;      // bf16 kernel: heads that one die walks together, tile by tile (0: all its heads)
 };
 
-// Kernel arguments of the backward pass (bf16, Hq == Hk).
+// Kernel arguments of the backward pass (bf16; Hq / Hk query heads share a key/value head).
 struct BwdParams {
   const void* Q;
   const void* Kseq;
@@ -52,6 +52,7 @@ struct BwdParams {
   void* dKdepth;
   void* dVdepth;
   float* rowstat;  // workspace: (LSE_t * log2(e), <dO_t, O_t>) per row, [B, Hq, T, 2]
+  float* dq_depth;  // workspace: the depth slots' share of dQ, fp32, not yet scaled, [B, Hq, T, d]
   int B, Hq, Hk, T;
   int depth_alloc, depth_count;
   int causal;

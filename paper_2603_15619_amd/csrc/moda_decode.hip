@@ -239,14 +239,15 @@ static hipError_t launch_decode_d(DecodeParams p, hipStream_t stream) {
   const int gt = G >= 8 ? 8 : G >= 4 ? 4 : G >= 2 ? 2 : 1;
   const int n_gc = (G + gt - 1) / gt;
   const long long blocks = (long long)p.B * p.Hk * n_gc * p.n_split;
-  if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (!grid_ok(blocks) || !grid_ok((long long)p.B * p.Hq)) return kGridTooLarge;
   dim3 grid((unsigned)blocks), block(kDecWaves * 64);
-  if (gt == 8) hipLaunchKernelGGL((moda_decode_partial_kernel<D, 8>), grid, block, 0, stream, p);
-  else if (gt == 4) hipLaunchKernelGGL((moda_decode_partial_kernel<D, 4>), grid, block, 0, stream, p);
-  else if (gt == 2) hipLaunchKernelGGL((moda_decode_partial_kernel<D, 2>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((moda_decode_partial_kernel<D, 1>), grid, block, 0, stream, p);
-  hipLaunchKernelGGL(moda_decode_merge_kernel<D>, dim3((unsigned)(p.B * p.Hq)), dim3(D), 0, stream, p);
-  return hipGetLastError();
+  hipError_t e;
+  if (gt == 8) e = launch_kernel(moda_decode_partial_kernel<D, 8>, grid, block, stream, p);
+  else if (gt == 4) e = launch_kernel(moda_decode_partial_kernel<D, 4>, grid, block, stream, p);
+  else if (gt == 2) e = launch_kernel(moda_decode_partial_kernel<D, 2>, grid, block, stream, p);
+  else e = launch_kernel(moda_decode_partial_kernel<D, 1>, grid, block, stream, p);
+  if (e != hipSuccess) return e;
+  return launch_kernel(moda_decode_merge_kernel<D>, dim3((unsigned)(p.B * p.Hq)), dim3(D), stream, p);
 }
 
 hipError_t launch_decode_bf16(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,

@@ -45,10 +45,9 @@ hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void*
   const int cpr = row_bytes / 16;
   const long long n_chunks = rows * cpr;
   const long long blocks = (n_chunks + 256 * kAppendPerThread - 1) / (256 * kAppendPerThread);
-  if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(moda_depth_append_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const char*)K,
-                     (const char*)V, (char*)Kdepth, (char*)Vdepth, n_chunks, cpr, depth_alloc, slot);
-  return hipGetLastError();
+  if (!grid_ok(blocks)) return kGridTooLarge;
+  return launch_kernel(moda_depth_append_kernel, dim3((unsigned)blocks), dim3(256), stream, (const char*)K,
+                       (const char*)V, (char*)Kdepth, (char*)Vdepth, n_chunks, cpr, depth_alloc, slot);
 }
 
 }  // namespace moda

@@ -475,8 +475,11 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int rg = lane / LPR;
     const int l16 = lane % LPR;       // owns channels 8*l16 .. 8*l16+7
     const size_t drow = (size_t)p.depth_alloc * C::kRowBytes;  // bytes of one position's slots
-    const char* Kdb = (const char*)p.Kdepth + (size_t)bg * T * drow;
-    const char* Vdb = (const char*)p.Vdepth + (size_t)bg * T * drow;
+    // The depth slots are addressed from the tile's first position (a 64-bit base per tile) with
+    // 32-bit offsets inside the tile: the depth tensors may be of any size.
+    const size_t dtile = ((size_t)bg * T + q0) * drow;
+    const char* Kdb = (const char*)p.Kdepth + dtile;
+    const char* Vdb = (const char*)p.Vdepth + dtile;
     // In this phase wave w takes 32 / GT positions x all GT heads of the tile, heads fastest:
     // the rows of one load instruction that share a position fetch the same depth slots, so a
     // group's slots come from memory once per tile, not once per head.  A row's state lives in
@@ -548,8 +551,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       u32x4 k[kDepthChunk], v[kDepthChunk];
     };
     const int nch = (L + kDepthChunk - 1) / kDepthChunk;
-    // The depth slabs are read through raw buffers with 32-bit offsets.
-    const size_t slab_bytes = (size_t)T * drow;
+    // ... through raw buffers that end with the (batch, head) slab (clamped to what 32 bits hold;
+    // a tile never reaches that far).
+    const size_t left = (size_t)(T - q0) * drow;
+    const size_t slab_bytes = left < 0xffffffffull ? left : 0xffffffffull;
     const __amdgpu_buffer_rsrc_t kd_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void*)Kdb, 0, (int)(unsigned)slab_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t vd_buf = __builtin_amdgcn_make_buffer_rsrc(
@@ -558,7 +563,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       const Row rw = row_at(it);
       const int tc = min(q0 + rw.pos, T - 1);  // rows past the end use row T-1, never stored
       buf.q = *(const u32x4*)((const char*)p.Q + ((size_t)(hb + rw.head) * T + tc) * C::kRowBytes + l16 * 16);
-      const int voff = (int)((unsigned)tc * (unsigned)drow + (unsigned)l16 * 16u);  // < 4 GiB per slab (checked by the host)
+      const int voff = (int)((unsigned)(tc - q0) * (unsigned)drow + (unsigned)l16 * 16u);  // a tile's slots stay far below 4 GiB (depth_alloc is limited by the host)
       // slots of the chunk past depth_count re-read the last attended slot (a cache hit, ignored)
       // rather than fetching bytes that nothing uses
 #pragma unroll
@@ -975,19 +980,13 @@ hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t str
   const int tile_pos = waves * kQPerWave / gt;
   if (p.n_qtiles != (p.T + tile_pos - 1) / tile_pos) return hipErrorInvalidValue;
   const long long blocks = (long long)p.B * (p.Hq / gt) * p.n_qtiles;
-  if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (!grid_ok(blocks)) return kGridTooLarge;
   dim3 grid((unsigned)blocks), block(waves * 64);
-  if (d == 128 && waves == 8)
-    hipLaunchKernelGGL((moda_fwd_bf16_kernel<128, 8>), grid, block, 0, stream, p);
-  else if (d == 128)
-    hipLaunchKernelGGL((moda_fwd_bf16_kernel<128, 4>), grid, block, 0, stream, p);
-  else if (d == 64 && waves == 8)
-    hipLaunchKernelGGL((moda_fwd_bf16_kernel<64, 8>), grid, block, 0, stream, p);
-  else if (d == 64)
-    hipLaunchKernelGGL((moda_fwd_bf16_kernel<64, 4>), grid, block, 0, stream, p);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
+  if (d == 128 && waves == 8) return launch_kernel(moda_fwd_bf16_kernel<128, 8>, grid, block, stream, p);
+  if (d == 128) return launch_kernel(moda_fwd_bf16_kernel<128, 4>, grid, block, stream, p);
+  if (d == 64 && waves == 8) return launch_kernel(moda_fwd_bf16_kernel<64, 8>, grid, block, stream, p);
+  if (d == 64) return launch_kernel(moda_fwd_bf16_kernel<64, 4>, grid, block, stream, p);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace moda

@@ -116,15 +116,11 @@ namespace moda {
 hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream) {
   const long long rows = (long long)p.B * p.Hq * p.T;
   const long long blocks = (rows + 3) / 4;
-  if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (!grid_ok(blocks)) return kGridTooLarge;
   dim3 grid((unsigned)blocks), block(256);
-  if (d == 128)
-    hipLaunchKernelGGL(moda_fwd_f32_kernel<128>, grid, block, 0, stream, p);
-  else if (d == 64)
-    hipLaunchKernelGGL(moda_fwd_f32_kernel<64>, grid, block, 0, stream, p);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
+  if (d == 128) return launch_kernel(moda_fwd_f32_kernel<128>, grid, block, stream, p);
+  if (d == 64) return launch_kernel(moda_fwd_f32_kernel<64>, grid, block, stream, p);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace moda

@@ -4,6 +4,21 @@
 
 namespace moda {
 
+// Enqueues `kernel` and returns THIS launch's status (hipLaunchKernel's own return value; the
+// thread's sticky "last error", which earlier work of the caller may have set, is not read).
+template <class... Params, class... Args>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+  static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+  return [&](Params... a) {
+    void* argv[] = {(void*)&a...};
+    return hipLaunchKernel((const void*)kernel, grid, block, argv, 0, stream);
+  }(args...);
+}
+// A grid that does not fit a launch: reported before anything is enqueued (the C ABI turns it
+// into MODA_ERR_UNSUPPORTED).
+constexpr hipError_t kGridTooLarge = hipErrorInvalidConfiguration;
+inline bool grid_ok(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
+
 // bf16 forward kernel: `waves` (8 or 4) waves per workgroup, 32 queries each; p.n_qtiles
 // must be the number of such tiles in p.T.
 int fwd_bf16_tile_rows(int waves);
@@ -13,7 +28,8 @@ hipError_t launch_fwd_f32(const FwdParams& p, int d, hipStream_t stream);
 // Backward (bf16, Hq / Hk <= bwd_bf16_max_group()): delta, [depth slots of grouped queries,]
 // dK/dV and dQ(/depth) kernels on `stream`.
 int bwd_bf16_max_group();
-size_t bwd_bf16_workspace_bytes(const BwdParams& p);
+int bwd_bf16_kernels(const BwdParams& p);  // kernels one call enqueues
+size_t bwd_bf16_workspace_bytes(const BwdParams& p, int d);
 hipError_t launch_bwd_bf16(const BwdParams& p, int d, hipStream_t stream);
 
 // Depth-stream write step: rows of K / V [rows, row_bytes] into slot `slot` of
@@ -28,5 +44,11 @@ hipError_t launch_decode_bf16(const void* Q, const void* Kseq, const void* Vseq,
                               const void* Vdepth, void* O, float* LSE, float* ws, int B, int Hq, int Hk, int T,
                               int T_alloc, int d, int depth_alloc, int depth_count, float scale,
                               hipStream_t stream);
+
+// Matrix-pipe calibration kernel (moda_calibrate.hip).
+size_t calibrate_operand_bytes();
+size_t calibrate_sink_bytes(int workgroups);
+double calibrate_flops(int workgroups, int iters);
+hipError_t launch_calibrate_mfma(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);
 
 }  // namespace moda

@@ -60,6 +60,59 @@ def make_inputs(B, Hq, Hk, T, d, depth_count, dtype="bf16", seed=0, device="cpu"
     return out
 
 
+def make_structured_inputs(kind, B, Hq, Hk, T, d, depth_count, seed=0, device="cpu", depth_alloc=None,
+                           with_dO=False, scale=None, slope=0.15, excess_log2=6.5, tile=64):
+    """bf16 inputs whose LOGITS have a chosen structure (the iid N(0,1) recipe of make_inputs
+    never makes a later key tile dominate an earlier one, so an online softmax's rescaling step
+    is hardly exercised).  `scale` is the softmax scale the call will use (default 1/sqrt(d)).
+    Starting from make_inputs' tensors:
+      "rising"         the sequence keys' logits rise by about `slope` (natural-log units) per
+                       key position: every key tile's maximum exceeds the previous one's by
+                       slope * tile, the running maximum is raised on every tile and earlier
+                       contributions are scaled down by large factors;
+      "plateau"        the logits of the keys from the second tile on sit about `excess_log2`
+                       powers of two above those of the first tile (a maximum that was fixed on
+                       the first tile stays below what follows, by a bounded amount);
+      "depth_dominant" depth slot 0 of every position is a multiple of the query itself (of the
+                       first query head of its group): its logit towers over all others;
+      "seq_dominant"   every depth key is a negative multiple of the query: the depth slots'
+                       weights vanish next to the sequence keys'.
+    Only Q, Kseq and Kdepth are shaped; values stay N(0,1)."""
+    import math
+
+    inp = make_inputs(B, Hq, Hk, T, d, depth_count, dtype="bf16", seed=seed, device=device,
+                      depth_alloc=depth_alloc, with_dO=with_dO)
+    sc = float(scale) if scale else 1.0 / math.sqrt(d)
+    qmag = 4.0
+    pos = torch.arange(T, device=device, dtype=torch.float32).view(1, 1, T, 1)
+    if kind in ("rising", "plateau"):
+        # Q = qmag in every channel + noise; a key whose channels all hold c then has the logit
+        # sc * qmag * d * c (+ noise terms): c is chosen per position
+        if kind == "rising":
+            c = slope * pos / (sc * qmag * d)
+            knoise = 0.5
+        else:
+            c = (pos >= tile).float() * (excess_log2 * math.log(2.0)) / (sc * qmag * d)
+            knoise = 0.02
+        inp["Q"] = (qmag + 0.25 * inp["Q"].float()).to(torch.bfloat16)
+        inp["Kseq"] = (c + knoise * inp["Kseq"].float()).to(torch.bfloat16)
+        if inp["Kdepth"] is not None and kind == "plateau":
+            inp["Kdepth"] = (knoise * inp["Kdepth"].float()).to(torch.bfloat16)
+    elif kind in ("depth_dominant", "seq_dominant"):
+        if inp["Kdepth"] is None:
+            raise ValueError("%s needs depth slots" % kind)
+        G = Hq // Hk
+        q0 = inp["Q"][:, ::G].float()  # first query head of every group, [B,Hk,T,d]
+        if kind == "depth_dominant":
+            inp["Kdepth"][:, :, :, 0] = (2.0 * q0).to(torch.bfloat16)
+        else:
+            qall = inp["Q"].float().view(B, Hk, G, T, d).mean(dim=2)
+            inp["Kdepth"] = (-2.0 * G * qall.unsqueeze(3) + 0.1 * inp["Kdepth"].float()).to(torch.bfloat16)
+    else:
+        raise ValueError("unknown kind %r" % kind)
+    return inp
+
+
 def to_f64(t):
     """Exact upcast of a torch tensor (any device, bf16/f32) to a float64 numpy array."""
     if t is None:

@@ -109,23 +109,39 @@ def test_new_entry_points_reject_bad_arguments_without_gpu(L):
     assert bwd(MODAShape(**dict(ok, dtype=0))) == 3
     assert bwd(MODAShape(**ok), ws_bytes=8) == 6
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 1) == 4               # grouped queries + depth slots
-    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 6  # 20 heads per group: 3 launches of 8
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 4  # 20 heads per group: still one depth kernel
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=2))), 1) == 3
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 0) == 1
 
 
-def test_slab_size_limit_without_gpu(L):
-    """One (batch, head) slab of any tensor must stay below 4 GiB (the kernels use 32-bit byte
-    offsets inside a slab): the largest accepted depth cache and the first rejected one."""
-    from paper_2603_15619_amd.binding import MODAShape
+def test_size_limits_without_gpu(L):
+    """One (batch, head) slab of a SEQUENCE tensor must stay below 4 GiB (32-bit byte offsets
+    inside a slab); the depth tensors have no such limit (64-bit tile bases), only a cap on the
+    slots per position; the decoding step addresses its caches with 64-bit pointers."""
+    from paper_2603_15619_amd.binding import MODAFwdTuning, MODAShape
 
     p = ctypes.c_void_p(0x1000)
-    base = dict(B=1, Hq=1, Hk=1, T=65536, d=128, depth_count=1, causal=1, scale=0.0, dtype=1)
+    base = dict(B=1, Hq=1, Hk=1, d=128, depth_count=1, causal=1, scale=0.0, dtype=1)
 
-    def fwd_status(depth_alloc):
-        s = MODAShape(depth_alloc=depth_alloc, **base)
+    def fwd_status(T, depth_alloc):
+        s = MODAShape(T=T, depth_alloc=depth_alloc, **base)
         # NULL output pointer: a shape that passes validation stops at the pointer check
         return L.moda_attn_fwd(p, p, p, p, p, None, p, ctypes.byref(s), None)
 
-    assert fwd_status(255) == 1   # 65536 * 255 * 128 * 2 bytes < 4 GiB: shape accepted (then NULL output)
-    assert fwd_status(256) == 3   # exactly 4 GiB: unsupported
+    assert fwd_status(65536, 256) == 1          # 4 GiB of depth slots per head: accepted (then NULL output)
+    assert fwd_status(131072, 8192) == 1
+    assert fwd_status(65536, 8193) == 3         # more slots per position than the cap
+    assert fwd_status((1 << 24) - 1, 1) == 1    # T * 128 * 2 bytes just below 4 GiB
+    assert fwd_status(1 << 24, 1) == 3          # exactly 4 GiB: unsupported
+
+    s = MODAShape(T=1 << 20, depth_alloc=256, **base)
+    assert L.moda_attn_decode(p, p, p, p, p, None, p, 1 << 25, p, 1 << 30, ctypes.byref(s), None) == 1
+
+    ok = MODAShape(B=1, Hq=4, Hk=2, T=16, d=128, depth_alloc=0, depth_count=0, causal=1, scale=0.0, dtype=1)
+
+    def tuned(**kw):
+        return L.moda_attn_fwd_tuned(p, p, p, None, None, None, p, ctypes.byref(ok), ctypes.byref(MODAFwdTuning(**kw)),
+                                     None)
+
+    assert tuned(waves=8, heads_per_tile=2, head_group=1) == 1   # accepted (then NULL output)
+    assert tuned(waves=5) == 2 and tuned(heads_per_tile=4) == 2 and tuned(head_group=-2) == 2

@@ -15,21 +15,23 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": (2e-2, 1e-3), "f32": (1e-5, 1e-5)}
 
 
-def run_gpu(inp, depth_count, causal=True, scale=None):
+def run_gpu(inp, depth_count, causal=True, scale=None, tuning=None):
     from paper_2603_15619_amd import moda_attn_fwd
 
     O, LSE = moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], inp["Kdepth"], inp["Vdepth"],
-                           depth_count=depth_count, causal=causal, scale=scale)
+                           depth_count=depth_count, causal=causal, scale=scale, tuning=tuning)
     torch.cuda.synchronize()
     return O, LSE
 
 
-def check_full(B, Hq, Hk, T, d, L, dtype, seed, causal=True, depth_alloc=None, scale=None):
+def check_full(B, Hq, Hk, T, d, L, dtype, seed, causal=True, depth_alloc=None, scale=None, tuning=None,
+               inp=None):
     print("case", dict(B=B, Hq=Hq, Hk=Hk, T=T, d=d, L=L, dtype=dtype, seed=seed, causal=causal,
-                       depth_alloc=depth_alloc), flush=True)
-    inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=seed, device="cuda",
-                            depth_alloc=depth_alloc)
-    O, LSE = run_gpu(inp, L, causal, scale)
+                       depth_alloc=depth_alloc, tuning=tuning), flush=True)
+    if inp is None:
+        inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=seed, device="cuda",
+                                depth_alloc=depth_alloc)
+    O, LSE = run_gpu(inp, L, causal, scale, tuning)
     Oref, Lref = R.fwd(*(synth.to_f64(inp[k]) for k in ("Q", "Kseq", "Vseq", "Kdepth", "Vdepth")),
                        depth_count=L, causal=causal, scale=scale)
     eo = np.abs(synth.to_f64(O) - Oref).max() if O.numel() else 0.0
@@ -40,16 +42,17 @@ def check_full(B, Hq, Hk, T, d, L, dtype, seed, causal=True, depth_alloc=None, s
     return eo, el
 
 
-def check_sampled(B, Hq, Hk, T, d, L, dtype, seed, n_random=48):
+def check_sampled(B, Hq, Hk, T, d, L, dtype, seed, n_random=48, inp=None, scale=None, tile=256):
     """Full-size problem: compare the rows the oracle can afford, for every (b, h)."""
     print("sampled case", dict(B=B, Hq=Hq, Hk=Hk, T=T, d=d, L=L, dtype=dtype, seed=seed), flush=True)
-    inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=seed, device="cuda")
-    O, LSE = run_gpu(inp, L)
-    rows = synth.sample_rows(T, n_random=n_random, edge=4, tile=256, seed=seed)
+    if inp is None:
+        inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype=dtype, seed=seed, device="cuda")
+    O, LSE = run_gpu(inp, L, scale=scale)
+    rows = synth.sample_rows(T, n_random=n_random, edge=4, tile=tile, seed=seed)
     ridx = torch.from_numpy(rows.astype(np.int64)).cuda()
     pick = lambda t: None if t is None else synth.to_f64(t.index_select(2, ridx))
     Oref, Lref = R.fwd_rows(pick(inp["Q"]), synth.to_f64(inp["Kseq"]), synth.to_f64(inp["Vseq"]),
-                            pick(inp["Kdepth"]), pick(inp["Vdepth"]), rows, depth_count=L)
+                            pick(inp["Kdepth"]), pick(inp["Vdepth"]), rows, depth_count=L, scale=scale)
     eo = np.abs(pick(O) - Oref).max()
     el = np.abs(pick(LSE) - Lref).max()
     print("   rows=%d  max|dO| = %.3e   max|dLSE| = %.3e" % (len(rows), eo, el), flush=True)
@@ -76,13 +79,12 @@ def test_bf16_shapes(T, d, L):
 
 @pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("T,d,L", [(1500, 128, 15), (1100, 64, 6), (129, 128, 2), (2048, 128, 0)])
-def test_bf16_both_geometries(monkeypatch, waves, T, d, L):
+def test_bf16_both_geometries(waves, T, d, L):
     """The bf16 kernel has two workgroup geometries (8 waves with 4-stage K/V rings, 4 waves
-    with 2-stage rings), normally chosen from the grid size; here each is forced on shapes
-    that span many key tiles, so that every ring stage is reused several times, and both
-    orders of the depth phase (before / after the key loop) occur."""
-    monkeypatch.setenv("MODA_FWD_WAVES", str(waves))
-    check_full(2, 4, 2, T, d, L, "bf16", 400 + T + waves)
+    with 2-stage rings), normally chosen from the grid size; here each is forced (through
+    moda_attn_fwd_tuned) on shapes that span many key tiles, so that every ring stage is reused
+    several times, and both orders of the depth phase (before / after the key loop) occur."""
+    check_full(2, 4, 2, T, d, L, "bf16", 400 + T + waves, tuning=dict(waves=waves))
 
 
 @pytest.mark.parametrize("T,d,L", [(300, 128, 5), (130, 64, 17), (1, 64, 2)])
@@ -193,3 +195,35 @@ def test_paper_kernel_benchmark_shape_sampled():
     """The shape family of the paper's kernel benchmark (Table 2): B=1, Hq=64, Hk=8 (G=8), d=64,
     64 depth slots, here at T=16384 on sampled rows of every head."""
     check_sampled(1, 64, 8, 16384, 64, 64, "bf16", 5, n_random=12)
+
+
+@pytest.mark.parametrize("G,Hk,T,L", [(8, 8, 4096, 128), (8, 8, 2048, 256), (32, 8, 2048, 64), (16, 8, 4096, 64)])
+def test_paper_table2_slot_counts_and_groups_sampled(G, Hk, T, L):
+    """The other axes of the paper's Table 2 (d = 64, H_k = 8): 128 and 256 depth slots at G = 8
+    (rows 12, 13) and groups of 16 and 32 query heads at 64 slots (rows 9, 10), on sampled rows of
+    every head.  (Sequence lengths are shorter than the table's 16384 so that the checker's share
+    stays within seconds; the tile structure, the number of slot chunks and the head subsets per
+    group are the table's.)"""
+    check_sampled(1, G * Hk, Hk, T, 64, L, "bf16", 6, n_random=6)
+
+
+def test_tuning_is_validated():
+    from paper_2603_15619_amd import MODAError, moda_attn_fwd
+
+    inp = synth.make_inputs(1, 4, 2, 64, 128, 0, dtype="bf16", seed=15, device="cuda")
+    for bad in (dict(waves=3), dict(waves=8, heads_per_tile=3), dict(head_group=-1), dict(heads_per_tile=4)):
+        with pytest.raises(MODAError):
+            moda_attn_fwd(inp["Q"], inp["Kseq"], inp["Vseq"], tuning=bad)
+    O0, L0 = run_gpu(inp, 0)
+    O1, L1 = run_gpu(inp, 0, tuning=dict(waves=8, heads_per_tile=1, head_group=1))
+    assert (O0.float() - O1.float()).abs().max().item() <= 2e-2
+
+
+def test_depth_tensors_beyond_4gib_per_head():
+    """One (batch, head) slab of the depth tensors larger than 4 GiB (T * depth_alloc * d * 2
+    bytes): tiles address their slots from a 64-bit base.  Checked on sampled rows, the last
+    ones (beyond the 4 GiB mark) among them."""
+    B, Hq, Hk, T, d, L = 1, 1, 1, 65536, 128, 260
+    inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype="bf16", seed=16, device="cuda")
+    assert inp["Kdepth"][0, 0].numel() * 2 > 1 << 32
+    check_sampled(B, Hq, Hk, T, d, L, "bf16", 16, n_random=8, inp=inp)
