@@ -6,7 +6,8 @@
  * allocates, frees or keeps a pointer; its only scratch is the workspace the
  * caller passes to the backward and decoding calls.  Calls are asynchronous on
  * the given HIP stream (NULL = the default stream), never synchronise the
- * device, read no environment variable and hold no global mutable state.
+ * device, read no environment variable and hold no global mutable state (one
+ * exception, stated at moda_attn_decode_noalloc).
  * Errors are reported by return code only.  Every argument check (pointers,
  * shapes, alignment, workspace size, the size of every kernel grid) is made
  * before the first kernel is enqueued: on any status other than MODA_OK and
@@ -176,6 +177,26 @@ size_t moda_attn_decode_workspace_bytes(const moda_shape* s);
 moda_status moda_attn_decode(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
                              const void* Vdepth, void* O, float* LSE, int32_t kv_alloc, void* workspace,
                              size_t workspace_bytes, const moda_shape* s, void* hip_stream);
+
+/*
+ * The decoding step for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operator, arguments and results as moda_attn_decode, but the slices' partial results go
+ * to a scratch array that is part of the library image (a file-scope device array of
+ * moda_attn_decode_noalloc_max_bytes() = 8 MiB; every GPU the library runs on holds its own
+ * copy until the process ends).  The call allocates nothing and frees nothing.  A shape whose
+ * moda_attn_decode_workspace_bytes() exceeds that size is rejected with MODA_ERR_WORKSPACE
+ * before anything is launched (use moda_attn_decode with a workspace then).  All calls on one
+ * GPU share that GPU's array: two such calls that overlap in time on the same GPU (different
+ * streams, different threads) race and give wrong results; calls on one stream, or otherwise
+ * ordered, are safe, and nothing in the array needs clearing between calls.  The array's device
+ * address is looked up once per GPU, on the first call made with that GPU current; that per-GPU
+ * address table is the only state the library keeps.
+ */
+size_t moda_attn_decode_noalloc_max_bytes(void);
+moda_status moda_attn_decode_noalloc(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                                     const void* Vdepth, void* O, float* LSE, int32_t kv_alloc,
+                                     const moda_shape* s, void* hip_stream);
 
 /*
  * Measurement aid: a kernel whose loop holds nothing but the bf16 matrix instruction the

@@ -15,7 +15,8 @@ LIB_PATH = os.environ.get("MODA_LIB_PATH") or os.path.join(HERE, "libmoda.so")
 
 MODA_F32, MODA_BF16 = 0, 1
 EXPORTS = ("moda_attn_fwd", "moda_attn_fwd_tuned", "moda_attn_bwd_workspace_bytes", "moda_attn_bwd", "moda_depth_append",
-           "moda_attn_decode", "moda_attn_decode_workspace_bytes",
+           "moda_attn_decode", "moda_attn_decode_workspace_bytes", "moda_attn_decode_noalloc",
+           "moda_attn_decode_noalloc_max_bytes",
            "moda_calibrate_mfma", "moda_calibrate_mfma_operand_bytes", "moda_calibrate_mfma_sink_bytes",
            "moda_status_string", "moda_version", "moda_kernels_per_call")
 
@@ -64,6 +65,10 @@ def lib():
         L.moda_attn_decode_workspace_bytes.restype = ctypes.c_size_t
         L.moda_attn_decode.argtypes = [vp] * 7 + [ctypes.c_int32, vp, ctypes.c_size_t, sp, vp]
         L.moda_attn_decode.restype = ctypes.c_int
+        L.moda_attn_decode_noalloc.argtypes = [vp] * 7 + [ctypes.c_int32, sp, vp]
+        L.moda_attn_decode_noalloc.restype = ctypes.c_int
+        L.moda_attn_decode_noalloc_max_bytes.argtypes = []
+        L.moda_attn_decode_noalloc_max_bytes.restype = ctypes.c_size_t
         L.moda_calibrate_mfma_operand_bytes.argtypes = []
         L.moda_calibrate_mfma_operand_bytes.restype = ctypes.c_size_t
         L.moda_calibrate_mfma_sink_bytes.argtypes = [ctypes.c_int32]
@@ -215,10 +220,12 @@ def moda_depth_append(K, V, Kdepth, Vdepth, slot):
 
 
 def moda_attn_decode(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, T=None, depth_count=None, scale=None,
-                     out=None, lse=None, workspace=None):
+                     out=None, lse=None, workspace=None, noalloc=False):
     """O [B,Hq,d], LSE [B,Hq] for one new token per sequence: Q [B,Hq,d]; sequence cache
     Kseq/Vseq [B,Hk,kv_alloc,d] of which positions [0, T) are attended (default: all); the new
-    token's depth slots Kdepth/Vdepth [B,Hk,depth_alloc,d] or None."""
+    token's depth slots Kdepth/Vdepth [B,Hk,depth_alloc,d] or None.  noalloc=True calls
+    moda_attn_decode_noalloc (the library's own scratch array instead of a workspace; `out`
+    and `lse` must then be given, so that this wrapper allocates nothing either)."""
     B, Hq, d = Q.shape
     Hk, kv_alloc = Kseq.shape[1], Kseq.shape[2]
     T = kv_alloc if T is None else int(T)
@@ -231,12 +238,19 @@ def moda_attn_decode(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, T=None, depth_coun
     _require(Kdepth, "Kdepth", (B, Hk, La, d), dt, dev)
     _require(Vdepth, "Vdepth", (B, Hk, La, d), dt, dev)
     s = MODAShape(B, Hq, Hk, T, d, La, L, 1, float(scale) if scale else 0.0, _dtype_code(Q))
+    if noalloc and (out is None or lse is None):
+        raise ValueError("noalloc=True needs out= and lse=")
     if out is None:
         out = torch.empty_like(Q)
     if lse is None:
         lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
     _require(out, "out", Q.shape, dt, dev)
     _require(lse, "lse", (B, Hq), torch.float32, dev)
+    if noalloc:
+        with torch.cuda.device(dev):
+            _check(lib().moda_attn_decode_noalloc(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth),
+                                                  _ptr(out), _ptr(lse), int(kv_alloc), ctypes.byref(s), _stream(dev)))
+        return out, lse
     need = int(lib().moda_attn_decode_workspace_bytes(ctypes.byref(s)))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

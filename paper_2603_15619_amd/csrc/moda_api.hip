@@ -205,6 +205,27 @@ moda_status moda_attn_decode(const void* Q, const void* Kseq, const void* Vseq, 
   return decode_with(Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, kv_alloc, workspace, s, hip_stream);
 }
 
+size_t moda_attn_decode_noalloc_max_bytes(void) { return moda::decode_static_scratch_bytes(); }
+
+moda_status moda_attn_decode_noalloc(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
+                                     const void* Vdepth, void* O, float* LSE, int32_t kv_alloc,
+                                     const moda_shape* s, void* hip_stream) {
+  moda_status st = check_decode(s, kv_alloc);
+  if (st != MODA_OK) return st;
+  if (moda_attn_decode_workspace_bytes(s) > moda::decode_static_scratch_bytes()) return MODA_ERR_WORKSPACE;
+  if (s->B == 0) return MODA_OK;
+  if (!Q || !Kseq || !Vseq || !O || !LSE) return MODA_ERR_NULL;
+  if (s->depth_count > 0 && (!Kdepth || !Vdepth)) return MODA_ERR_NULL;
+  const void* ptrs[] = {Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return MODA_ERR_ALIGN;
+  void* ws = nullptr;  // this GPU's copy of the library's scratch array (device address)
+  if (moda::decode_static_scratch(&ws) != hipSuccess) return MODA_ERR_LAUNCH;
+  // Nothing in the scratch has to start at zero: the first kernel writes every partial result
+  // that the second one reads.
+  return decode_with(Q, Kseq, Vseq, Kdepth, Vdepth, O, LSE, kv_alloc, ws, s, hip_stream);
+}
+
 static moda_status decode_with(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
                                const void* Vdepth, void* O, float* LSE, int32_t kv_alloc, void* workspace,
                                const moda_shape* s, void* hip_stream) {

@@ -12,11 +12,43 @@
 //            normalises, stores O and LSE.
 // Vector ALUs only (one query row per head: no matrix shape to speak of); a lane owns 8
 // channels, d/8 lanes a key row, 64 / (d/8) key rows per wave instruction.
+#include <atomic>
+
 #include "moda_launch.h"
 
 namespace moda {
 
 constexpr int kDecWaves = 4;
+
+// Scratch of the entry point that allocates nothing (moda_attn_decode_noalloc): the partial
+// results of the slices, which the caller's workspace holds otherwise.  One copy per GPU, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress:
+// kernels get the device address that call returns, never the name.
+constexpr size_t kDecodeScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kDecodeScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_addr[kMaxDevices];  // device address of `scratch`, per device (0: not looked up yet)
+
+size_t decode_static_scratch_bytes() { return kDecodeScratchBytes; }
+
+// Device address of `scratch` on the CURRENT device: looked up once per device (on the first
+// call made with that device current), then served from the table.
+hipError_t decode_static_scratch(void** addr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_addr[dev].store(p, std::memory_order_release);  // (two threads racing here store the same address)
+  }
+  *addr = p;
+  return hipSuccess;
+}
 
 struct DecodeParams {
   const void* Q;       // [B, Hq, d]

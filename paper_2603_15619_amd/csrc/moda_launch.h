@@ -40,6 +40,10 @@ hipError_t launch_depth_append(const void* K, const void* V, void* Kdepth, void*
 // Decoding step (one new token per sequence), bf16: partial kernel over slices of the sequence
 // cache + merge kernel; `ws` holds decode_workspace_bytes(...) bytes.
 size_t decode_workspace_bytes(int B, int Hq, int Hk, int T, int d);
+// The library's own scratch for the decoding step (a file-scope device array, one per GPU): its
+// size, and its device address on the current device.
+size_t decode_static_scratch_bytes();
+hipError_t decode_static_scratch(void** addr);
 hipError_t launch_decode_bf16(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
                               const void* Vdepth, void* O, float* LSE, float* ws, int B, int Hq, int Hk, int T,
                               int T_alloc, int d, int depth_alloc, int depth_count, float scale,
