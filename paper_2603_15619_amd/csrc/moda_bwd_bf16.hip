@@ -741,30 +741,57 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p)
   }
 }
 
-// Sum over the lanes that differ from this one in the lane-index bits >= log2(FROM) (FROM = 8
-// or 16): lane l, l ^ FROM, l ^ 2 FROM, ..., i.e. over the 64 / FROM lanes with equal l % FROM.
-template <int FROM>
-__device__ __forceinline__ float sum_across_groups(float x) {
-  if (FROM == 8) x += dpp_mov<0x128>(x);  // row_ror:8 inside a row of 16 lanes = lane ^ 8
-  {                                       // lane ^ 16: the two rows of each half swap
-    const int xi = __builtin_bit_cast(int, x);
-    auto r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
-    x = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
+// Reduce-scatter over the head lanes of the wide kernel below.  On entry every lane holds 16
+// partial sums x[0..15] (x[0..7]: dVdepth channels 0..7 of its 8-channel chunk, x[8..15]: the
+// same for dKdepth) of ITS head; the sums over the 64 / LPR heads that sit side by side (lanes
+// with equal lane % LPR) are wanted.  Each step halves the number of values a lane is
+// responsible for and adds the partner's share of those: lane ^ 32 (lanes < 32 keep dV, the
+// others dK), lane ^ 16 (keeps channels 0..3 or 4..7) and, with 8 lanes per head (d = 64),
+// lane ^ 8 (keeps channels 0,1 or 2,3 of those).  On return x[0], x[1] (d = 64) or x[0..3]
+// (d = 128) hold the fully reduced values of
+//   tensor  (lane >> 5)               0: dVdepth, 1: dKdepth
+//   channel 8 * (lane % LPR) + 4 * ((lane >> 4) & 1) [+ 2 * ((lane >> 3) & 1) at d = 64] + j.
+template <int LPR>
+__device__ __forceinline__ void reduce_scatter_heads(float (&x)[16], int lane) {
+  // lane ^ 32: one swap moves the halves of two values at once (low lanes give away x[8 + j],
+  // high lanes x[j])
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, x[j]), __builtin_bit_cast(int, x[8 + j]), false, false);
+    x[j] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
   }
-  return pair_sum(x);                     // lane ^ 32
+  // lane ^ 16: rows of 16 lanes swap (even rows give away x[4 + j], odd rows x[j])
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(int, x[j]), __builtin_bit_cast(int, x[4 + j]), false, false);
+    x[j] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
+  }
+  if (LPR == 8) {
+    // lane ^ 8 (a rotation by 8 inside a row of 16 lanes): lanes with bit 3 clear keep x[j],
+    // the others x[2 + j]
+    const bool up = (lane & 8) != 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float keep = up ? x[2 + j] : x[j], give = up ? x[j] : x[2 + j];
+      x[j] = keep + dpp_mov<0x128>(give);
+    }
+  }
 }
 
 // Groups of more than 8 query heads (8 < G <= 64).  One WAVE = one (batch, key/value head,
 // position); lane = (head within a set of HS = 64 / (d/8) heads, 8 channels): the heads of a set
 // work side by side, NS = ceil(G / HS) sets one after the other.  Per slot the lanes of a head
 // reduce the two dot products over its channels, the head's contributions to dKdepth_i and
-// dVdepth_i are summed over the sets in registers and over the heads of a set across lanes, in
-// fp32, and rounded once; each head's depth share of dQ stays in registers over the slots and
-// goes to the workspace in fp32.  RESIDENT: the heads' Q / dO rows stay in registers (NS <= 8);
-// otherwise they are re-read (from the caches) for every slot.
+// dVdepth_i are summed over the sets in registers and over the heads of a set across lanes
+// (reduce_scatter_heads), in fp32, and rounded once; each head's depth share of dQ stays in
+// registers over the slots and goes to the workspace in fp32.  RESIDENT: the heads' Q / dO rows
+// stay in registers, unpacked to fp32 (NS <= 4) or packed (NS = 8); otherwise they are re-read
+// (from the caches) for every slot.
 template <int D, int NS, bool RESIDENT>
 __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams p) {
   constexpr int LPR = D / 8, HS = 64 / LPR, RB = D * 2;
+  constexpr bool UNPACKED = RESIDENT && NS <= 4;
+  constexpr int NOUT = LPR == 8 ? 2 : 4;  // reduced values per lane and slot
   const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
   const int lane = threadIdx.x & 63, l16 = lane % LPR, hs = lane / LPR;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b * Hk + g) * T + t
@@ -777,12 +804,22 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams 
   // head of set s on this lane: s * HS + hs (heads past the group repeat the last one, weight zero)
   auto head_row = [&](int s) { return (size_t)(bh0 + min(s * HS + hs, G - 1)) * T + t; };
   u32x4 q[RESIDENT ? NS : 1], g[RESIDENT ? NS : 1];
+  float qx[UNPACKED ? NS : 1][8], gx[UNPACKED ? NS : 1][8];
   float l2[NS], dl[NS], dq[NS][8];
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     if (RESIDENT) {
       q[s] = *(const u32x4*)((const char*)p.Q + head_row(s) * RB + l16 * 16);
       g[s] = *(const u32x4*)((const char*)p.dO + head_row(s) * RB + l16 * 16);
+    }
+    if (UNPACKED) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        qx[s][2 * k] = bf16_lo(q[s][k]);
+        qx[s][2 * k + 1] = bf16_hi(q[s][k]);
+        gx[s][2 * k] = bf16_lo(g[s][k]);
+        gx[s][2 * k + 1] = bf16_hi(g[s][k]);
+      }
     }
     const f32x2 st = *(const f32x2*)(p.rowstat + head_row(s) * 2);
     l2[s] = st[0];
@@ -793,8 +830,11 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams 
   const size_t drow = (size_t)La * RB;
   const char* kd = (const char*)p.Kdepth + (size_t)row * drow + l16 * 16;
   const char* vd = (const char*)p.Vdepth + (size_t)row * drow + l16 * 16;
-  char* dkd = (char*)p.dKdepth + (size_t)row * drow + l16 * 16;
-  char* dvd = (char*)p.dVdepth + (size_t)row * drow + l16 * 16;
+  // where this lane's reduced values go (see reduce_scatter_heads): NOUT channels of one tensor
+  const int out_ch = 8 * l16 + 4 * ((lane >> 4) & 1) + (LPR == 8 ? 2 * ((lane >> 3) & 1) : 0);
+  const bool is_dk = lane >= 32;
+  char* outp = (char*)(is_dk ? p.dKdepth : p.dVdepth) + (size_t)row * drow + out_ch * 2;
+  const float out_scale = is_dk ? p.scale : 1.0f;
 
   // two slots in flight ahead of the one being worked on
   u32x4 kn[2], vn[2];
@@ -810,14 +850,14 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams 
     const int inext = min(i + 2, L - 1);
     kn[1] = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
     vn[1] = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
-    float kx[8], ak[8], av[8];
+    float kx[8], x[16];  // x[0..7]: dVdepth partial sums, x[8..15]: dKdepth partial sums (unscaled)
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       kx[2 * k] = bf16_lo(kv[k]);
       kx[2 * k + 1] = bf16_hi(kv[k]);
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) ak[k] = av[k] = 0.f;
+    for (int k = 0; k < 16; ++k) x[k] = 0.f;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       u32x4 qs, gs;
@@ -839,35 +879,26 @@ __global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams 
       const float pe = s * HS + hs < G ? fast_exp2(sdot * c2 - l2[s]) : 0.f;
       const float e = pe * (gdot - dl[s]);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        av[2 * k] += pe * bf16_lo(gs[k]);
-        av[2 * k + 1] += pe * bf16_hi(gs[k]);
-        ak[2 * k] += e * bf16_lo(qs[k]);
-        ak[2 * k + 1] += e * bf16_hi(qs[k]);
+      for (int k = 0; k < 8; ++k) {
+        const float gk = UNPACKED ? gx[s][k] : ((k & 1) ? bf16_hi(gs[k >> 1]) : bf16_lo(gs[k >> 1]));
+        const float qk = UNPACKED ? qx[s][k] : ((k & 1) ? bf16_hi(qs[k >> 1]) : bf16_lo(qs[k >> 1]));
+        x[k] += pe * gk;
+        x[8 + k] += e * qk;
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) dq[s][k] += e * kx[k];
     }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      av[k] = sum_across_groups<LPR>(av[k]);
-      ak[k] = sum_across_groups<LPR>(ak[k]);
-    }
-    if (hs == 0) {
-      const float f = p.scale;
-      const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
-      const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
-                        pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
-      __builtin_nontemporal_store(o1, (u32x4*)(dvd + (size_t)i * RB));
-      __builtin_nontemporal_store(o2, (u32x4*)(dkd + (size_t)i * RB));
+    reduce_scatter_heads<LPR>(x, lane);
+    if (NOUT == 2) {
+      *(uint32_t*)(outp + (size_t)i * RB) = pack_bf16(x[0] * out_scale, x[1] * out_scale);
+    } else {
+      *(u32x2*)(outp + (size_t)i * RB) = (u32x2){pack_bf16(x[0] * out_scale, x[1] * out_scale),
+                                                 pack_bf16(x[2] * out_scale, x[3] * out_scale)};
     }
   }
-  if (hs == 0) {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
-      *(u32x4*)(dvd + (size_t)i * RB) = z;
-      *(u32x4*)(dkd + (size_t)i * RB) = z;
-    }
+  for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
+    if (NOUT == 2) *(uint32_t*)(outp + (size_t)i * RB) = 0u;
+    else *(u32x2*)(outp + (size_t)i * RB) = (u32x2){0u, 0u};
   }
 #pragma unroll
   for (int s = 0; s < NS; ++s)
