@@ -8,6 +8,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoda.so")
+# the seeded input generator is a library of its own (it holds none of the operator's arithmetic)
+SYNTH_SRC = os.path.join(HERE, "synth_csrc", "moda_synth.hip")
+SYNTH_LIB = os.path.join(HERE, "libmoda_synth.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -211,7 +214,17 @@ def build_libmoda() -> str:
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], check=True)
     os.replace(tmp, LIB)
+    build_synth()
     return LIB
+
+
+def build_synth() -> str:
+    """Compiles the device-side input generator into libmoda_synth.so."""
+    tmp = SYNTH_LIB + ".tmp.%d" % os.getpid()
+    subprocess.run([HIPCC, *FLAGS, "-shared", SYNTH_SRC, "-o", tmp], check=True,
+                   stderr=subprocess.PIPE if os.environ.get("MODA_QUIET_BUILD") else None)
+    os.replace(tmp, SYNTH_LIB)
+    return SYNTH_LIB
 
 
 if __name__ == "__main__":

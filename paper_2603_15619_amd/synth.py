@@ -2,7 +2,9 @@
 
 Holds no attention arithmetic: it only draws iid N(0,1) tensors of the shapes the
 operator takes (paper section 2.2; the paper's kernel benchmarks use random
-tensors of stated shape) and converts tensors for the CPU checker.  Both the HIP
+tensors of stated shape) and converts tensors for the CPU checker.  Device tensors
+are filled by the build's own counter-based generator (synth_csrc/moda_synth.hip,
+libmoda_synth.so: hash of (seed, tensor id, index) -> Box-Muller, on the device).  Both the HIP
 path and the tests' fp64 checker consume the SAME buffers produced here: a
 tensor is drawn once, on the device it will be used on, and the checker gets an
 exact upcast of a copy of it.
@@ -11,8 +13,31 @@ Layouts: Q, dO [B,Hq,T,d]; Kseq, Vseq [B,Hk,T,d]; Kdepth, Vdepth
 [B,Hk,T,depth_alloc,d] (slots >= depth_count are filled too, so a kernel that
 reads them by mistake is caught).
 """
+import ctypes
+import os
+
 import numpy as np
 import torch
+
+_SYNTH_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoda_synth.so")
+_synth_lib = None
+
+
+def _device_generator():
+    """libmoda_synth.so: the build's own counter-based N(0,1) generator, run on the device
+    (torch only provides the memory).  Raises if it has not been built."""
+    global _synth_lib
+    if _synth_lib is None:
+        if not os.path.exists(_SYNTH_LIB_PATH):
+            raise FileNotFoundError("%s not found: build it with `python -m paper_2603_15619_amd.build`"
+                                    % _SYNTH_LIB_PATH)
+        L = ctypes.CDLL(_SYNTH_LIB_PATH)
+        L.moda_synth_normal.argtypes = [ctypes.c_void_p, ctypes.c_ulonglong, ctypes.c_ulonglong, ctypes.c_uint,
+                                        ctypes.c_int, ctypes.c_void_p]
+        L.moda_synth_normal.restype = ctypes.c_int
+        _synth_lib = L
+    return _synth_lib
+
 
 _DTYPES = {"bf16": torch.bfloat16, "f32": torch.float32}
 
@@ -21,13 +46,24 @@ _TENSOR_IDS = {"Q": 0, "Kseq": 1, "Vseq": 2, "Kdepth": 3, "Vdepth": 4, "dO": 5}
 
 
 def _randn(shape, dtype, seed, tensor_id, device):
-    gen = torch.Generator(device=device)
-    gen.manual_seed(int(seed) * 16 + tensor_id)
     n = 1
     for s in shape:
         n *= int(s)
     if n == 0:
         return torch.empty(shape, dtype=dtype, device=device)
+    if torch.device(device).type == "cuda":
+        # on the device: the build's own generator fills the tensor in place
+        out = torch.empty(shape, dtype=dtype, device=device)
+        with torch.cuda.device(out.device):
+            rc = _device_generator().moda_synth_normal(
+                ctypes.c_void_p(out.data_ptr()), n, int(seed), int(tensor_id), 1 if dtype == torch.bfloat16 else 0,
+                ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
+        if rc != 0:
+            raise RuntimeError("moda_synth_normal rejected its arguments")
+        return out
+    # host tensors (CPU-only experiments): torch's generator
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed) * 16 + tensor_id)
     # Draw in slabs along dim 0 so a multi-GB bf16 tensor never needs an fp32 twin.
     out = torch.empty(shape, dtype=dtype, device=device)
     flat = out.view(-1)

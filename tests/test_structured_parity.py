@@ -45,8 +45,16 @@ def test_fwd_structured(kind, kw, d, waves):
 @pytest.mark.parametrize("d,scale", [(128, 1.0), (64, 0.75)])
 def test_fwd_large_scale(d, scale):
     """iid N(0,1) inputs with a softmax scale far above 1/sqrt(d): logits of standard deviation
-    ~sqrt(d) * scale, a few keys carry each row."""
-    check_fwd_full(2, 4, 2, 1300, d, 7, "bf16", 720 + d, scale=scale)
+    ~sqrt(d) * scale, one or two keys carry each row, so |O| reaches the largest |V| (about 5 among
+    a million N(0,1) values) instead of the ~0.1 of the task's configurations.  The task's 2e-2 is
+    stated for those; here the bound is what bf16 arithmetic guarantees for values of that size:
+    weights rounded to bf16 (relative 2^-8, at most 2^-8 max|V| on the weighted sum) plus the
+    output's own rounding (2^-8 |O|), i.e. 2 * 2^-8 * max|V| (3.9e-2 at 5); the measured error
+    is about 2e-2."""
+    B, Hq, Hk, T, L, seed = 2, 4, 2, 1300, 7, 720 + d
+    inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype="bf16", seed=seed, device="cuda")
+    vmax = max(inp["Vseq"].abs().max().item(), inp["Vdepth"].abs().max().item())
+    check_fwd_full(B, Hq, Hk, T, d, L, "bf16", seed, scale=scale, inp=inp, tol_o=2 * 2.0 ** -8 * vmax)
 
 
 @pytest.mark.parametrize("kind,kw", [("rising", dict(slope=0.15)), ("plateau", dict(excess_log2=7.0))])
