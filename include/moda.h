@@ -105,15 +105,18 @@ moda_status moda_attn_fwd(const void* Q, const void* Kseq, const void* Vseq, con
  * code path; the result is the same operator whatever the geometry).  A field that is 0
  * keeps the library's own choice; `tuning` == NULL is moda_attn_fwd.
  *   waves           4 or 8: waves (of 32 queries each) per workgroup
- *   heads_per_tile  query heads of one group that share a tile; divides both Hq / Hk and
- *                   `waves`
+ *   heads_per_tile  query heads of one group that share a tile (side by side in every wave): a
+ *                   power of two up to 32 that divides Hq / Hk
  *   head_group      (batch, head) units that one die walks together, tile by tile; >= 1
+ *   depth_path      1: depth slots on the vector ALUs (row-major dot products); 2: on the
+ *                   matrix pipe (per-wave key blocks)
  * Values that the kernel cannot run are rejected with MODA_ERR_SHAPE.  Ignored for fp32.
  */
 typedef struct {
   int32_t waves;
   int32_t heads_per_tile;
   int32_t head_group;
+  int32_t depth_path;
 } moda_fwd_tuning;
 moda_status moda_attn_fwd_tuned(const void* Q, const void* Kseq, const void* Vseq, const void* Kdepth,
                                 const void* Vdepth, void* O, float* LSE, const moda_shape* s,

@@ -29,7 +29,8 @@ class MODAShape(ctypes.Structure):
 
 
 class MODAFwdTuning(ctypes.Structure):
-    _fields_ = [("waves", ctypes.c_int32), ("heads_per_tile", ctypes.c_int32), ("head_group", ctypes.c_int32)]
+    _fields_ = [("waves", ctypes.c_int32), ("heads_per_tile", ctypes.c_int32), ("head_group", ctypes.c_int32),
+                ("depth_path", ctypes.c_int32)]
 
 
 class MODAError(RuntimeError):
@@ -138,7 +139,7 @@ def moda_attn_fwd(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, depth_count=None, cau
 
     Q [B,Hq,T,d]; Kseq/Vseq [B,Hk,T,d]; Kdepth/Vdepth [B,Hk,T,depth_alloc,d] or
     None; slots [0, depth_count) of each position are attended (default: all).
-    `tuning` = dict(waves=, heads_per_tile=, head_group=) calls moda_attn_fwd_tuned (the bf16
+    `tuning` = dict(waves=, heads_per_tile=, head_group=, depth_path=) calls moda_attn_fwd_tuned (the bf16
     kernel's launch geometry chosen by the caller; missing keys keep the library's choice).
     """
     s = make_shape(Q, Kseq, Kdepth, depth_count, causal, scale)
@@ -160,7 +161,7 @@ def moda_attn_fwd(Q, Kseq, Vseq, Kdepth=None, Vdepth=None, depth_count=None, cau
                                        _ptr(out), _ptr(lse), ctypes.byref(s), _stream(dev)))
         else:
             tn = MODAFwdTuning(int(tuning.get("waves", 0)), int(tuning.get("heads_per_tile", 0)),
-                               int(tuning.get("head_group", 0)))
+                               int(tuning.get("head_group", 0)), int(tuning.get("depth_path", 0)))
             _check(lib().moda_attn_fwd_tuned(_ptr(Q), _ptr(Kseq), _ptr(Vseq), _ptr(Kdepth), _ptr(Vdepth),
                                              _ptr(out), _ptr(lse), ctypes.byref(s), ctypes.byref(tn), _stream(dev)))
     return out, lse

@@ -115,8 +115,9 @@ moda_status moda_attn_fwd_tuned(const void* Q, const void* Kseq, const void* Vse
     if (tuning->waves != 0 && tuning->waves != 4 && tuning->waves != 8) return MODA_ERR_SHAPE;
     if (tuning->waves != 0) waves = tuning->waves;
     const int gt = tuning->heads_per_tile;
-    if (gt < 0 || (gt > 0 && (waves % gt != 0 || G % gt != 0))) return MODA_ERR_SHAPE;
+    if (gt < 0 || gt > 32 || (gt & (gt - 1)) != 0 || (gt > 0 && G % gt != 0)) return MODA_ERR_SHAPE;
     if (tuning->head_group < 0) return MODA_ERR_SHAPE;
+    if (tuning->depth_path < 0 || tuning->depth_path > 2) return MODA_ERR_SHAPE;
   }
   if (s->B == 0 || s->T == 0) return MODA_OK;
   if (!Q || !Kseq || !Vseq || !O || !LSE) return MODA_ERR_NULL;
@@ -133,9 +134,10 @@ moda_status moda_attn_fwd_tuned(const void* Q, const void* Kseq, const void* Vse
   p.causal = s->causal;
   p.scale = resolve_scale(s);
   p.scale_log2 = p.scale * 1.4426950408889634f;
-  // grouped queries: as many heads of a group per tile as divide both the group and the waves
+  // grouped queries: as many heads of a group per tile (side by side in every wave) as divide the
+  // group, up to 32
   p.heads_per_tile = 1;
-  for (int gt = waves; gt > 1; gt /= 2)
+  for (int gt = 32; gt > 1; gt /= 2)
     if (G % gt == 0) {
       p.heads_per_tile = gt;
       break;
@@ -143,6 +145,13 @@ moda_status moda_attn_fwd_tuned(const void* Q, const void* Kseq, const void* Vse
   if (tuning && tuning->heads_per_tile > 0) p.heads_per_tile = tuning->heads_per_tile;
   p.head_group = heads_per_die_at_a_time((long long)s->B * s->Hk * (G / p.heads_per_tile), s->T, s->d);
   if (tuning && tuning->head_group > 0) p.head_group = tuning->head_group;
+  // depth slots: on the matrix pipe when several heads share a position's slots (the block
+  // products are then dense enough to beat the vector ALUs), else on the vector ALUs, where the
+  // phase already runs at the rate a compute unit can fetch
+  p.depth_mfma = (p.heads_per_tile > 1 && s->depth_count > 0) ? 1 : 0;
+  if (tuning && s->dtype == MODA_BF16 && tuning->depth_path != 0)
+    p.depth_mfma = (tuning->depth_path == 2 && s->depth_count > 0) ? 1 : 0;
+  p.depth_magic = s->depth_count > 1 ? (unsigned)((1ull << 32) / (unsigned)s->depth_count) + 1u : 0u;
   const int rows = moda::fwd_bf16_tile_rows(waves) / p.heads_per_tile;  // positions per tile
   p.n_qtiles = (s->T + rows - 1) / rows;
 

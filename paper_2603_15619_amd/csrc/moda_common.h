@@ -34,6 +34,8 @@ struct FwdParams {
   int n_qtiles;      // tiles along the sequence (bf16 kernel: see heads_per_tile)
   int heads_per_tile;  // bf16 kernel: query heads of one group that share a tile (divides Hq/Hk and the waves)
   int head_group;      // bf16 kernel: heads that one die walks together, tile by tile (0: all its heads)
+  int depth_mfma;      // bf16 kernel: depth slots on the matrix pipe (1) or on the vector ALUs (0)
+  unsigned depth_magic;  // bf16 kernel: floor(2^32 / depth_count) + 1, so that umulhi(k, magic) = k / depth_count
 };
 
 // Kernel arguments of the backward pass (bf16; Hq / Hk query heads share a key/value head).

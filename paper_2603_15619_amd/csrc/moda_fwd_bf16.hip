@@ -400,11 +400,13 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- What this workgroup computes.  A tile is kBM (position, query head) pairs of one
-  // key/value head: kBM / GT consecutive positions x GT query heads of its group (GT divides
-  // both the group size and the number of waves; GT = 1 without grouped queries).  All rows of
-  // the tile read the same sequence K/V tiles and, position by position, the same depth slots
-  // (the paper flattens the G heads of a group into the row axis for the same reason).  Wave w
-  // owns head w % GT and the 32 positions of block w / GT in the key loop.
+  // key/value head: kBM / GT consecutive positions x GT query heads of its group (GT a power of
+  // two up to 32 that divides the group size; GT = 1 without grouped queries).  All rows of the
+  // tile read the same sequence K/V tiles and, position by position, the same depth slots (the
+  // paper flattens the G heads of a group into the row axis for the same reason).  Wave w owns
+  // the 32 / GT positions w * 32 / GT ... and all GT heads: its query l (a column of the matrix
+  // products) is position l / GT, head l % GT, so that the depth slots of a position, which only
+  // the queries at that position attend, are needed by one wave only.
   // Heavy (late) tiles first; consecutive workgroup ids walk over (batch, key/value head,
   // head subset), so that, with ids dealt round-robin to the 8 dies, one die keeps serving the
   // same heads and its L2 sees each K/V tile from several workgroups.
@@ -440,10 +442,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int T = p.T;
   const int tile_pos = kBM / GT;          // positions per tile
   const int q0 = qt * tile_pos;
-  const int qw0 = q0 + (wave / GT) * kQPerWave;
-  const int bh = hb + wave % GT;          // this wave's head in the key loop
+  const int PW = kQPerWave / GT;          // positions per wave
+  const int gt_shift = __builtin_ctz(GT);
+  const int qw0 = q0 + wave * PW;         // the wave's first position
 
-  const char* Qb = (const char*)p.Q + (size_t)bh * T * C::kRowBytes;
   const char* Kb = (const char*)p.Kseq + (size_t)bg * T * C::kRowBytes;
   const char* Vb = (const char*)p.Vseq + (size_t)bg * T * C::kRowBytes;
 
@@ -480,11 +482,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const size_t dtile = ((size_t)bg * T + q0) * drow;
     const char* Kdb = (const char*)p.Kdepth + dtile;
     const char* Vdb = (const char*)p.Vdepth + dtile;
-    // In this phase wave w takes 32 / GT positions x all GT heads of the tile, heads fastest:
-    // the rows of one load instruction that share a position fetch the same depth slots, so a
-    // group's slots come from memory once per tile, not once per head.  A row's state lives in
-    // the exchange buffer of the wave that owns it in the key loop (hence the barriers around
-    // this phase).
+    // As in the key loop, wave w takes 32 / GT positions x all GT heads of the tile, heads
+    // fastest: the rows of one load instruction that share a position fetch the same depth slots,
+    // so a group's slots come from memory once per tile, not once per head.  Row r of the wave
+    // is column r of its matrix products: its state is row r of the wave's own exchange buffer.
     struct Row {
       int head;  // within the tile
       int pos;   // within the tile
@@ -493,14 +494,15 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       const int r = it * RPS + rg;
       return Row{r % GT, wave * (kQPerWave / GT) + r / GT};
     };
-    auto state_of = [&](Row r) { return smem + ((r.pos / kQPerWave) * GT + r.head) * C::kXWave; };
+    auto state_of = [&](Row) { return smem + wave * C::kXWave; };
+    auto row_in_wave = [&](Row r) { return (r.pos - wave * PW) * GT + r.head; };
 
     // row state in the row-major mapping
     float o[8], m = 0.f, l = 1.f;
     auto begin_row = [&](Row rw) {
       unsigned char* xw = state_of(rw);
       float* ml = (float*)(xw + 32 * C::kXRow);
-      const int row = rw.pos % kQPerWave;
+      const int row = row_in_wave(rw);
       if constexpr (MODE == 1) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) o[k] = 0.f;
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     auto end_row = [&](Row rw) {
       unsigned char* xw = state_of(rw);
       float* ml = (float*)(xw + 32 * C::kXRow);
-      const int row = rw.pos % kQPerWave;
+      const int row = row_in_wave(rw);
       if constexpr (MODE == 1) {
         *(f32x4*)(xw + row * C::kXRow + l16 * 32) = (f32x4){o[0], o[1], o[2], o[3]};
         *(f32x4*)(xw + row * C::kXRow + l16 * 32 + 16) = (f32x4){o[4], o[5], o[6], o[7]};
@@ -665,7 +667,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   // half computes.  The result does not depend on the order (one softmax over the union).
   // Workgroup ids are dealt round-robin to the 8 dies: the role alternates within a die.
   const bool depth_first = L > 0 && ((blockIdx.x >> 3) & 1) != 0;
-  if (depth_first) {
+  // Two implementations of the depth slots: on the vector ALUs in the row-major mapping
+  // (depth_phase above), or on the matrix pipe as extra key blocks (depth_blocks below).
+  const bool depth_on_mfma = p.depth_mfma != 0;
+  if (depth_first && !depth_on_mfma) {
     depth_phase(kDepthFirst);
     __syncthreads();  // rows were written into the buffers of the waves that own them
   }
@@ -676,16 +681,17 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   {
     i32x4 qtmp[C::kDSteps];  // all loads are issued before the first one is consumed
     const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
-    const int row = min(qw0 + l32, T - 1);
+    const int row = min(qw0 + (l32 >> gt_shift), T - 1);
+    const char* Qb = (const char*)p.Q + ((size_t)(hb + (l32 & (GT - 1))) * T + row) * C::kRowBytes;
 #pragma unroll
     for (int st = 0; st < C::kDSteps; ++st)
-      qtmp[st] = *(const i32x4*)(Qb + (size_t)row * C::kRowBytes + st * 32 + hi * 16);
+      qtmp[st] = *(const i32x4*)(Qb + st * 32 + hi * 16);
     MODA_PIN();
     static_for<C::kDSteps>([&](auto ST) { set_q<decltype(ST)::value>(qtmp[decltype(ST)::value]); });
   }
   float m_run = -INFINITY;  // reference max of the raw scores <q,k>
   float l_run = 0.f;        // this lane's share of the normaliser
-  if (depth_first) {
+  if (depth_first && !depth_on_mfma) {
     // state left by the depth slots, from the row-major exchange buffer into the accumulator
     // layout (the inverse of the epilogue's exchange); the lane pair (l, l ^ 32) shares a row:
     // both hold its reference max, one of them its normaliser
@@ -777,7 +783,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   auto mask_tile = [&](STile& s, int kt) {
     const int k0 = kt * kBN;
     const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
-    const int qi = qw0 + l32;
+    const int qi = qw0 + (l32 >> gt_shift);
     const int lim = p.causal ? min(qi, T - 1) : T - 1;  // last visible key
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -792,6 +798,143 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   FragBase<C> fb;
   fb.init(tid & 63, (int)smem_addr);
   float mx = 0.f;
+
+  // ---- The depth slots on the matrix pipe.  A wave's 32 queries are PW = 32 / GT consecutive
+  // positions x GT heads; the attended depth slots of those positions, enumerated position by
+  // position, are PW * L keys that only THIS wave needs, key kk belonging to position kk / L
+  // (and attended by the GT queries at that position: the matrix instructions do 32 / GT times
+  // the work a dense product would need).  They are taken
+  // 32 keys at a time exactly like a block of sequence keys - S^T = K Q^T, the same running
+  // (max, normaliser, output) in the same registers, O^T += V^T P^T - with the mask "key and query
+  // belong to the same position" (Algorithm 1's depth mask) in place of the causal one.  Each wave
+  // copies its own blocks global -> LDS into a private region of the (idle) K/V rings and waits
+  // for them alone: no workgroup barrier inside the phase, and the 8 waves together keep 8
+  // blocks in flight, which is what a compute unit can pull from HBM.  Slots >= depth_count are
+  // never fetched (a lane whose row is not an attended slot points outside the buffer and
+  // receives zeros), so they may hold anything.  Runs before the key loop (on an empty state) or
+  // after it.
+  auto depth_blocks = [&]() {
+    constexpr int PR = C::kPieceRows, NP = 32 / PR;  // rows per 1 KB piece, pieces per block
+    constexpr int kDK = NP * C::kKPieceStride, kDV = NP * C::kVPieceStride, kDWave = kDK + kDV;
+    static_assert(W * kDWave <= C::kLds, "one block per wave fits the rings");
+    static_assert(C::kDSteps <= kSlots && 2 * C::kDBlocks <= kSlots, "a block's fragments fit the slots");
+    const int lane = lane_id(), l32 = lane & 31, hi = lane >> 5;
+    const int nkeys = PW * L;
+    const int nblk = (nkeys + 31) >> 5;
+    const size_t drow = (size_t)p.depth_alloc * C::kRowBytes;
+    // raw buffers that start at the wave's first position (64-bit base) and end with the
+    // (batch, head) slab; a wave whose positions all lie past the end gets an empty buffer
+    const bool any = qw0 < T;
+    const size_t dbase = ((size_t)bg * T + (any ? qw0 : 0)) * drow;
+    const size_t left = any ? (size_t)(T - qw0) * drow : 0;
+    const unsigned recs = left < 0xffffff00ull ? (unsigned)left : 0xffffff00u;
+    const i32x4 kd_buf = make_raw_buffer((const char*)p.Kdepth + dbase, recs);
+    const i32x4 vd_buf = make_raw_buffer((const char*)p.Vdepth + dbase, recs);
+    const int dlds = __builtin_amdgcn_readfirstlane((int)smem_addr + wave * kDWave);
+    const int dwave = wave * kDWave;  // the same, as an addend to the per-lane fragment bases
+    // this lane's part of a copy: row j of the piece, chunk position pc (see the tile layouts)
+    const int j = lane / C::kChunks, pc = lane % C::kChunks;
+    const int vc = (((pc >> 2) ^ C::vswz(j)) << 2) | (pc & 3);
+    // K and V pieces of a block are requested separately: the K region is refilled as soon as the
+    // block's K fragments have been read (while its scores are still being computed), the V region
+    // as soon as its V^T fragments have been read, so that a wave always has the next block's
+    // other half in flight.  IS_K picks the tensor.
+    auto copy_half = [&](auto IS_K, int blk) {
+      constexpr bool is_k = decltype(IS_K)::value;
+      static_for<NP>([&](auto P) {
+        constexpr int pi = decltype(P)::value;
+        const int kc = C::kD == 128 ? (pc ^ (j & 3)) : (pc ^ (((pi & 1) * 4 + (j >> 1)) & (C::kChunks - 1)));
+        const unsigned kk = (unsigned)(blk * 32 + pi * PR + j);          // key in the wave's enumeration
+        const unsigned pos = L == 1 ? kk : __umulhi(kk, p.depth_magic);  // kk / L (exact for kk * L < 2^32)
+        const unsigned slot = kk - pos * (unsigned)L;
+        const unsigned rowoff = (pos * (unsigned)p.depth_alloc + slot) * (unsigned)C::kRowBytes;
+        const bool ok = kk < (unsigned)nkeys;
+        const int vo = ok ? (int)(rowoff + (is_k ? kc : vc) * 16) : (int)0xffffff80u;  // outside every buffer: zeros
+        if constexpr (is_k) copy16_to_lds<pi * C::kKPieceStride, 0, 0>(kd_buf, vo, 0, dlds);
+        else copy16_to_lds<kDK + pi * C::kVPieceStride, 0, 0>(vd_buf, vo, 0, dlds);
+      });
+    };
+    constexpr std::true_type kHalfK{};
+    constexpr std::false_type kHalfV{};
+    if (nblk > 0) {
+      copy_half(kHalfK, 0);
+      copy_half(kHalfV, 0);
+    }
+    for (int blk = 0; blk < nblk; ++blk) {
+      const bool more = blk + 1 < nblk;
+      // S^T = K Q^T over the block's 32 keys (the V copies of this block were issued after its K copies)
+      wait_copies_but<NP>();
+      STile sd;
+      static_for<C::kDSteps>([&](auto ST) {
+        constexpr int st = decltype(ST)::value;
+        if constexpr (C::kD == 128) read_k_slot<st % kSlots, (st >> 1) * 64>(fb.k[st & 1] + dwave);
+        else read_k_slot<st % kSlots, 0>(fb.k[st] + dwave);
+      });
+      lds_wait<0>();
+      static_for<C::kDSteps>([&](auto ST) {
+        constexpr int st = decltype(ST)::value;
+        mfma_s<st % kSlots, st, st == 0>(sd.a[0]);
+      });
+      if (more) copy_half(kHalfK, blk + 1);  // the K region has been read
+      MODA_PIN();
+      MODA_NOP(15);  // the matrix results have landed before the vector ALUs read them
+      MODA_NOP(15);
+      // mask: key r of the block is attended by this lane's query iff it is a slot of its position
+      const unsigned lo = (unsigned)((l32 >> gt_shift) * L - blk * 32);  // first key of the position, relative to the block
+      float vmax = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const unsigned r = (unsigned)((i >> 2) * 8 + hi * 4 + (i & 3));
+        const bool vis = (r - lo) < (unsigned)L;
+        sd.a[0][i] = vis ? sd.a[0][i] : -INFINITY;
+        vmax = fmaxf(vmax, sd.a[0][i]);
+      }
+      const float mxd = pair_max(vmax);
+      const bool raise = (mxd - m_run) * c2 > 8.f;  // false when the query has no key in this block
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        const float m_new = fmaxf(m_run, mxd);
+        // (a query that has seen no key yet keeps its empty state: -inf - -inf must not become NaN)
+        const float alpha = m_new == m_run ? 1.0f : fast_exp2((m_run - m_new) * c2);
+        m_run = m_new;
+        l_run *= alpha;
+        static_for<C::kDBlocks * 16>([&](auto R) { scale_acc<kAccO + decltype(R)::value>(alpha); });
+        MODA_PIN();
+        MODA_NOP(7);
+      }
+      const float mc = m_run == -INFINITY ? 0.f : m_run * c2;
+      PTile pd;
+      float lsum = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float e0 = fast_exp2(sd.a[0][2 * q] * c2 - mc);
+        const float e1 = fast_exp2(sd.a[0][2 * q + 1] * c2 - mc);
+        lsum += e0 + e1;
+        pd.a[0][q >> 2][q & 3] = (int)pack_bf16(e0, e1);
+      }
+      l_run += lsum;
+      // O^T += V^T P^T (the next block's K copies, if any, were issued after this block's V copies)
+      if (more) wait_copies_but<NP>();
+      else wait_copies_but<0>();
+      static_for<2 * C::kDBlocks>([&](auto F) {
+        constexpr int f = decltype(F)::value, ks = f / C::kDBlocks, db = f % C::kDBlocks;
+        read_v_slot<f % kSlots, ks * (16 / PR) * C::kVPieceStride, 8 / PR * C::kVPieceStride>(
+            fb.v[db] + (dwave + kDK - C::kVBase));
+      });
+      lds_wait<0>();
+      static_for<2 * C::kDBlocks>([&](auto F) {
+        constexpr int f = decltype(F)::value, ks = f / C::kDBlocks, db = f % C::kDBlocks;
+        mfma_o<db, f % kSlots>(pd.a[0][ks]);
+      });
+      if (more) copy_half(kHalfV, blk + 1);  // the V region has been read
+      MODA_PIN();
+    }
+    MODA_NOP(15);
+    lds_wait<0>();
+  };
+  if (depth_first && depth_on_mfma) {
+    depth_blocks();
+    __syncthreads();  // every wave is done with its region: the rings may be filled
+  }
 
   // ---- prologue: fill the rings, zero the V stage that stands in for "tile -1"
   // (its P is zero too, but 0 * garbage could be NaN), S(0) = K(0) Q^T.
@@ -938,6 +1081,10 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   lds_wait<0>();         // fragment reads requested but never used have landed
   wait_copies_but<0>();  // the ring is reused below: no copy may still be landing in it
   __syncthreads();
+  if (L > 0 && !depth_first && depth_on_mfma) {
+    depth_blocks();
+    __syncthreads();     // every wave is done with its region: the exchange buffers may be written
+  }
 
   // ================= epilogue: accumulator layout -> row-major, depth slots, store
   {
@@ -964,7 +1111,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   // From here on the accumulation registers are the compiler's (it parks depth K/V
   // loads in them); the build step checks that on the generated code.
   asm volatile("; MODA_ACC_REGISTERS_RELEASED" ::: "memory");
-  if (L == 0 || depth_first) depth_phase(kPlainStore);
+  if (L == 0 || depth_first || depth_on_mfma) depth_phase(kPlainStore);
   else depth_phase(kDepthLast);
 }
 
@@ -976,7 +1123,8 @@ int fwd_bf16_tile_rows(int waves) { return waves * kQPerWave; }
 
 hipError_t launch_fwd_bf16(const FwdParams& p, int d, int waves, hipStream_t stream) {
   const int gt = p.heads_per_tile;
-  if ((waves != 4 && waves != 8) || gt < 1 || waves % gt != 0 || (p.Hq / p.Hk) % gt != 0) return hipErrorInvalidValue;
+  if ((waves != 4 && waves != 8) || gt < 1 || gt > kQPerWave || (gt & (gt - 1)) != 0 || (p.Hq / p.Hk) % gt != 0)
+    return hipErrorInvalidValue;
   const int tile_pos = waves * kQPerWave / gt;
   if (p.n_qtiles != (p.T + tile_pos - 1) / tile_pos) return hipErrorInvalidValue;
   const long long blocks = (long long)p.B * (p.Hq / gt) * p.n_qtiles;

@@ -227,3 +227,34 @@ def test_depth_tensors_beyond_4gib_per_head():
     inp = synth.make_inputs(B, Hq, Hk, T, d, L, dtype="bf16", seed=16, device="cuda")
     assert inp["Kdepth"][0, 0].numel() * 2 > 1 << 32
     check_sampled(B, Hq, Hk, T, d, L, "bf16", 16, n_random=8, inp=inp)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("T,d,L,La", [(700, 128, 15, None), (530, 64, 33, None), (300, 128, 1, None), (257, 64, 5, 8),
+                                      (1000, 128, 64, 70)])
+def test_both_depth_paths(path, waves, T, d, L, La):
+    """The depth slots have two implementations in the bf16 kernel: dot products on the vector ALUs
+    (depth_path 1) and per-wave key blocks on the matrix pipe (depth_path 2, the default when a
+    tile holds one head).  Both are forced here on the same shapes, with ragged ends, slot counts
+    that do not fill a 32-key block, and allocated-but-unattended slots that hold NaN."""
+    inp = synth.make_inputs(2, 2, 2, T, d, L, dtype="bf16", seed=900 + T + path, device="cuda", depth_alloc=La)
+    if La is not None:
+        inp["Kdepth"][:, :, :, L:] = float("nan")
+        inp["Vdepth"][:, :, :, L:] = float("nan")
+    check_full(2, 2, 2, T, d, L, "bf16", 0, depth_alloc=La, tuning=dict(waves=waves, depth_path=path), inp=inp)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("Hq,Hk,gt,T,d,L,La", [(8, 1, 8, 300, 64, 9, None), (16, 2, 4, 257, 128, 5, 7), (32, 1, 32, 130, 64, 64, None),
+                                               (16, 1, 16, 200, 128, 33, None), (4, 2, 2, 700, 64, 15, None),
+                                               (64, 2, 32, 100, 128, 3, 4), (8, 1, 2, 333, 64, 70, None)])
+def test_grouped_queries_both_depth_paths(path, Hq, Hk, gt, T, d, L, La):
+    """Several query heads side by side in every wave (2 ... 32 of a group; a wave then holds
+    32 / gt positions), with the depth slots on the vector ALUs and on the matrix pipe: a position's
+    slots are attended by the gt queries at that position only."""
+    inp = synth.make_inputs(1, Hq, Hk, T, d, L, dtype="bf16", seed=950 + Hq + T + path, device="cuda", depth_alloc=La)
+    if La is not None:
+        inp["Kdepth"][:, :, :, L:] = float("nan")
+        inp["Vdepth"][:, :, :, L:] = float("nan")
+    check_full(1, Hq, Hk, T, d, L, "bf16", 0, depth_alloc=La, tuning=dict(heads_per_tile=gt, depth_path=path), inp=inp)
