@@ -23,8 +23,8 @@
 // Grouped-query attention (G = Hq / Hk query heads per key/value head, G <= 64): the
 // gradients of the shared keys and values sum over the group.  dkdv walks the query
 // tiles of all G heads; the depth-slot gradients are computed by a kernel of their own
-// (depth_gqa for G <= 8, depth_gqa_wide above) that holds the G heads of a position side by
-// side, sums in fp32 and rounds every depth gradient once.
+// (depth_gqa for G <= 8 on the vector ALUs, depth_group above that on the matrix pipe) that holds
+// the G heads of a position side by side, sums in fp32 and rounds every depth gradient once.
 #include <type_traits>
 
 #include "moda_launch.h"
@@ -741,172 +741,225 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p)
   }
 }
 
-// Reduce-scatter over the head lanes of the wide kernel below.  On entry every lane holds 16
-// partial sums x[0..15] (x[0..7]: dVdepth channels 0..7 of its 8-channel chunk, x[8..15]: the
-// same for dKdepth) of ITS head; the sums over the 64 / LPR heads that sit side by side (lanes
-// with equal lane % LPR) are wanted.  Each step halves the number of values a lane is
-// responsible for and adds the partner's share of those: lane ^ 32 (lanes < 32 keep dV, the
-// others dK), lane ^ 16 (keeps channels 0..3 or 4..7) and, with 8 lanes per head (d = 64),
-// lane ^ 8 (keeps channels 0,1 or 2,3 of those).  On return x[0], x[1] (d = 64) or x[0..3]
-// (d = 128) hold the fully reduced values of
-//   tensor  (lane >> 5)               0: dVdepth, 1: dKdepth
-//   channel 8 * (lane % LPR) + 4 * ((lane >> 4) & 1) [+ 2 * ((lane >> 3) & 1) at d = 64] + j.
-template <int LPR>
-__device__ __forceinline__ void reduce_scatter_heads(float (&x)[16], int lane) {
-  // lane ^ 32: one swap moves the halves of two values at once (low lanes give away x[8 + j],
-  // high lanes x[j])
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, x[j]), __builtin_bit_cast(int, x[8 + j]), false, false);
-    x[j] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
-  }
-  // lane ^ 16: rows of 16 lanes swap (even rows give away x[4 + j], odd rows x[j])
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(int, x[j]), __builtin_bit_cast(int, x[4 + j]), false, false);
-    x[j] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
-  }
-  if (LPR == 8) {
-    // lane ^ 8 (a rotation by 8 inside a row of 16 lanes): lanes with bit 3 clear keep x[j],
-    // the others x[2 + j]
-    const bool up = (lane & 8) != 0;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const float keep = up ? x[2 + j] : x[j], give = up ? x[j] : x[2 + j];
-      x[j] = keep + dpp_mov<0x128>(give);
-    }
-  }
-}
-
-// Groups of more than 8 query heads (8 < G <= 64).  One WAVE = one (batch, key/value head,
-// position); lane = (head within a set of HS = 64 / (d/8) heads, 8 channels): the heads of a set
-// work side by side, NS = ceil(G / HS) sets one after the other.  Per slot the lanes of a head
-// reduce the two dot products over its channels, the head's contributions to dKdepth_i and
-// dVdepth_i are summed over the sets in registers and over the heads of a set across lanes
-// (reduce_scatter_heads), in fp32, and rounded once; each head's depth share of dQ stays in
-// registers over the slots and goes to the workspace in fp32.  RESIDENT: the heads' Q / dO rows
-// stay in registers, unpacked to fp32 (NS <= 4) or packed (NS = 8); otherwise they are re-read
-// (from the caches) for every slot.
-template <int D, int NS, bool RESIDENT>
-__global__ __launch_bounds__(256) void moda_bwd_depth_gqa_wide_kernel(BwdParams p) {
-  constexpr int LPR = D / 8, HS = 64 / LPR, RB = D * 2;
-  constexpr bool UNPACKED = RESIDENT && NS <= 4;
-  constexpr int NOUT = LPR == 8 ? 2 : 4;  // reduced values per lane and slot
+// ---------------------------------------------------------------- depth-slot gradients of a large group, matrix pipe
+// Groups of more than 8 query heads (8 < G <= 64; the G * T rows of Q of a group must fit 32-bit
+// byte offsets, else the call is rejected as unsupported).
+// With that many heads per position the depth-slot gradients of ONE position are small dense
+// products (the paper's group-aware depth calculation, here for the backward):
+//   S  = Q_p Kd_p^T   [G x L]    dP = dO_p Vd_p^T
+//   P  = exp2(S c2 - lse2_h),    E  = P (dP - delta_h)
+//   dVd_p = P^T dO_p  [L x d],   dKd_p = scale E^T Q_p,   dQ_p (depth share) = E Kd_p  [G x d]
+// One workgroup of ONE wave per (batch, key/value head, position).  The G heads' Q and dO rows
+// of the position (rows of different heads, gathered) and 64 slots at a time of Kd_p, Vd_p are
+// copied global -> LDS into four 64-row tiles of the layout the other backward kernels use;
+// the score products are formed in both orientations (slots x heads for the product that
+// contracts over slots, heads x slots for the two that contract over heads), exactly as the
+// dK/dV and dQ kernels do for sequence keys.  Rows of the tiles beyond G heads / beyond
+// depth_count slots are filled with zeros by the bounds-checked copies (unattended slots are
+// never fetched) and get weight zero.  Sums in fp32 on the matrix pipe, one rounding per
+// gradient element.  Several such workgroups share a compute unit (32 KB of LDS each at d = 64),
+// which is what hides the latency of the copies.
+template <int D, int NG>
+__global__ __launch_bounds__(64) void moda_bwd_depth_group_kernel(BwdParams p) {
+  using Tl = Tile<D>;
+  constexpr int RB = D * 2;
+  constexpr int kRowsPerInst = 1024 / RB;       // rows one copy instruction moves
+  constexpr int kInst = 64 / kRowsPerInst;      // copy instructions per tile
+  constexpr int kStatOff = 4 * Tl::kBytes;      // (lse2, delta) per head row, after the four tiles
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * Tl::kBytes + 64 * 8];
+  const int lane = threadIdx.x, l32 = lane & 31, hi = lane >> 5;
   const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
-  const int lane = threadIdx.x & 63, l16 = lane % LPR, hs = lane / LPR;
-  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b * Hk + g) * T + t
-  if (row >= (long long)p.B * p.Hk * T) return;  // the whole wave leaves; no workgroup barrier below
+  const long long row = blockIdx.x;  // (b * Hk + g) * T + t
   const int t = (int)(row % T);
   const int bg = (int)(row / T);
   const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;
   const float c2 = p.scale_log2;
+  const unsigned smem_addr = (unsigned)(size_t)(lds_ptr)smem;
+  const unsigned q_tile = smem_addr, g_tile = smem_addr + Tl::kBytes, k_tile = smem_addr + 2 * Tl::kBytes,
+                 v_tile = smem_addr + 3 * Tl::kBytes;
+  float* stat = (float*)(smem + kStatOff);
+  FragAddr<D> fa;
+  fa.init(lane);
 
-  // head of set s on this lane: s * HS + hs (heads past the group repeat the last one, weight zero)
-  auto head_row = [&](int s) { return (size_t)(bh0 + min(s * HS + hs, G - 1)) * T + t; };
-  u32x4 q[RESIDENT ? NS : 1], g[RESIDENT ? NS : 1];
-  float qx[UNPACKED ? NS : 1][8], gx[UNPACKED ? NS : 1][8];
-  float l2[NS], dl[NS], dq[NS][8];
+  // ---- the heads' rows of this position: row h of the tile = head h of the group
+  const int j = lane / Tl::kChunks, pc = lane % Tl::kChunks;  // this lane's row in a piece, chunk position
+  {
+    const size_t base = ((size_t)bh0 * T + t) * RB;
+    const unsigned bytes = (unsigned)(((size_t)(G - 1) * T + 1) * RB);  // (< 0xffffff00, below the offset that stands for "no row": checked by the host)
+    const i32x4 q_buf = make_tile_buffer((const char*)p.Q + base, bytes);
+    const i32x4 g_buf = make_tile_buffer((const char*)p.dO + base, bytes);
 #pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    if (RESIDENT) {
-      q[s] = *(const u32x4*)((const char*)p.Q + head_row(s) * RB + l16 * 16);
-      g[s] = *(const u32x4*)((const char*)p.dO + head_row(s) * RB + l16 * 16);
+    for (int q = 0; q < kInst; ++q) {
+      const int h = q * kRowsPerInst + j;
+      const int c = pc ^ Tl::swz(h);
+      const int voff = h < G ? (int)((unsigned)h * (unsigned)T * (unsigned)RB + (unsigned)c * 16u) : (int)0xffffff80u;
+      tile_copy16(q_buf, voff, 0, q_tile + q * 1024);
+      tile_copy16(g_buf, voff, 0, g_tile + q * 1024);
     }
-    if (UNPACKED) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        qx[s][2 * k] = bf16_lo(q[s][k]);
-        qx[s][2 * k + 1] = bf16_hi(q[s][k]);
-        gx[s][2 * k] = bf16_lo(g[s][k]);
-        gx[s][2 * k + 1] = bf16_hi(g[s][k]);
-      }
-    }
-    const f32x2 st = *(const f32x2*)(p.rowstat + head_row(s) * 2);
-    l2[s] = st[0];
-    dl[s] = st[1];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) dq[s][k] = 0.f;
+    // heads past the group get lse2 = +inf: weight zero
+    const int h = lane;
+    f32x2 st = {INFINITY, 0.f};
+    if (h < G) st = *(const f32x2*)(p.rowstat + ((size_t)(bh0 + h) * T + t) * 2);
+    *(f32x2*)(stat + 2 * h) = st;
   }
+  f32x16 dqa[NG][Tl::kDBlocks];  // dQ^T (depth share): [head block][channel block], lane = head
+#pragma unroll
+  for (int hb = 0; hb < NG; ++hb)
+#pragma unroll
+    for (int cb = 0; cb < Tl::kDBlocks; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dqa[hb][cb][i] = 0.f;
+
   const size_t drow = (size_t)La * RB;
-  const char* kd = (const char*)p.Kdepth + (size_t)row * drow + l16 * 16;
-  const char* vd = (const char*)p.Vdepth + (size_t)row * drow + l16 * 16;
-  // where this lane's reduced values go (see reduce_scatter_heads): NOUT channels of one tensor
-  const int out_ch = 8 * l16 + 4 * ((lane >> 4) & 1) + (LPR == 8 ? 2 * ((lane >> 3) & 1) : 0);
-  const bool is_dk = lane >= 32;
-  char* outp = (char*)(is_dk ? p.dKdepth : p.dVdepth) + (size_t)row * drow + out_ch * 2;
-  const float out_scale = is_dk ? p.scale : 1.0f;
+  const char* kd = (const char*)p.Kdepth + (size_t)row * drow;
+  const char* vd = (const char*)p.Vdepth + (size_t)row * drow;
+  char* dkd = (char*)p.dKdepth + (size_t)row * drow;
+  char* dvd = (char*)p.dVdepth + (size_t)row * drow;
 
-  // two slots in flight ahead of the one being worked on
-  u32x4 kn[2], vn[2];
+  for (int c0 = 0; c0 < L; c0 += 64) {
+    // ---- 64 slots of this position (rows past depth_count: zeros)
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragment reads of the chunk before are complete
+    __builtin_amdgcn_wave_barrier();
+    {
+      const unsigned bytes = (unsigned)(min(64, L - c0) * RB);
+      const i32x4 k_buf = make_tile_buffer(kd + (size_t)c0 * RB, bytes);
+      const i32x4 v_buf = make_tile_buffer(vd + (size_t)c0 * RB, bytes);
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    kn[u] = L > 0 ? __builtin_nontemporal_load((const u32x4*)(kd + (size_t)min(u, L - 1) * RB)) : (u32x4){0u, 0u, 0u, 0u};
-    vn[u] = L > 0 ? __builtin_nontemporal_load((const u32x4*)(vd + (size_t)min(u, L - 1) * RB)) : (u32x4){0u, 0u, 0u, 0u};
-  }
-  for (int i = 0; i < L; ++i) {
-    const u32x4 kv = kn[0], vv = vn[0];
-    kn[0] = kn[1];
-    vn[0] = vn[1];
-    const int inext = min(i + 2, L - 1);
-    kn[1] = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
-    vn[1] = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
-    float kx[8], x[16];  // x[0..7]: dVdepth partial sums, x[8..15]: dKdepth partial sums (unscaled)
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      kx[2 * k] = bf16_lo(kv[k]);
-      kx[2 * k + 1] = bf16_hi(kv[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < 16; ++k) x[k] = 0.f;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      u32x4 qs, gs;
-      if (RESIDENT) {
-        qs = q[s];
-        gs = g[s];
-      } else {
-        qs = *(const u32x4*)((const char*)p.Q + head_row(s) * RB + l16 * 16);
-        gs = *(const u32x4*)((const char*)p.dO + head_row(s) * RB + l16 * 16);
+      for (int q = 0; q < kInst; ++q) {
+        const int r = q * kRowsPerInst + j;
+        const int voff = r * RB + ((pc ^ Tl::swz(r)) << 4);
+        tile_copy16(k_buf, voff, 0, k_tile + q * 1024);
+        tile_copy16(v_buf, voff, 0, v_tile + q * 1024);
       }
-      float sdot = 0.f, gdot = 0.f;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        sdot = dot2_bf16(qs[k], kv[k], sdot);
-        gdot = dot2_bf16(gs[k], vv[k], gdot);
-      }
-      sdot = group_sum<LPR>(sdot);
-      gdot = group_sum<LPR>(gdot);
-      const float pe = s * HS + hs < G ? fast_exp2(sdot * c2 - l2[s]) : 0.f;
-      const float e = pe * (gdot - dl[s]);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const float gk = UNPACKED ? gx[s][k] : ((k & 1) ? bf16_hi(gs[k >> 1]) : bf16_lo(gs[k >> 1]));
-        const float qk = UNPACKED ? qx[s][k] : ((k & 1) ? bf16_hi(qs[k >> 1]) : bf16_lo(qs[k >> 1]));
-        x[k] += pe * gk;
-        x[8 + k] += e * qk;
-      }
-#pragma unroll
-      for (int k = 0; k < 8; ++k) dq[s][k] += e * kx[k];
     }
-    reduce_scatter_heads<LPR>(x, lane);
-    if (NOUT == 2) {
-      *(uint32_t*)(outp + (size_t)i * RB) = pack_bf16(x[0] * out_scale, x[1] * out_scale);
-    } else {
-      *(u32x2*)(outp + (size_t)i * RB) = (u32x2){pack_bf16(x[0] * out_scale, x[1] * out_scale),
-                                                 pack_bf16(x[2] * out_scale, x[3] * out_scale)};
+    wait_copies();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const unsigned bq_row = fa.row + q_tile, bq_tr = fa.tr + q_tile, bq_tr8 = fa.tr8 + q_tile;
+    const unsigned bk_row = fa.row + k_tile, bk_tr = fa.tr + k_tile, bk_tr8 = fa.tr8 + k_tile;
+    constexpr int kGOff = Tl::kBytes;  // the dO tile follows the Q tile, the Vd tile the Kd tile
+
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      if (c0 + sb * 32 >= L) break;  // (uniform) no attended slot in this block
+      // dVd^T, dKd^T of the block's 32 slots: [channel block], lane = slot
+      f32x16 dva[Tl::kDBlocks], dka[Tl::kDBlocks];
+#pragma unroll
+      for (int cb = 0; cb < Tl::kDBlocks; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dva[cb][i] = dka[cb][i] = 0.f;
+#pragma unroll
+      for (int hb = 0; hb < NG; ++hb) {
+        if (hb * 32 >= G) break;  // (uniform)
+        // ---- slots x heads: S^T, dP^T (lane = head, registers = slots) -> E^T -> dQ^T += Kd^T E^T
+        {
+          f32x16 s, dp;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
+#pragma unroll
+          for (int st = 0; st < Tl::kDSteps; ++st) {
+            const unsigned xk = (unsigned)xor_here((int)bk_row, st << 5), xq = (unsigned)xor_here((int)bq_row, st << 5);
+            s = mfma_bf16(FragAddr<D>::row_frag(xk, sb, 0), FragAddr<D>::row_frag(xq, hb, 0), s);
+            dp = mfma_bf16(FragAddr<D>::row_frag(xk, sb, kGOff), FragAddr<D>::row_frag(xq, hb, kGOff), dp);
+          }
+          const f32x2 st_h = *(const f32x2*)(stat + 2 * (hb * 32 + l32));  // this lane's head
+          float ev[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int slot = c0 + sb * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
+            const float pe = slot < L ? fast_exp2(s[i] * c2 - st_h[0]) : 0.f;
+            ev[i] = pe * (dp[i] - st_h[1]);
+          }
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            float a8[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) a8[k] = ev[hf * 8 + k];
+            const bf16x8 eb = pack8(a8);
+#pragma unroll
+            for (int cb = 0; cb < Tl::kDBlocks; ++cb)
+              dqa[hb][cb] = mfma_bf16(FragAddr<D>::tr_frag((unsigned)xor_here((int)bk_tr, cb << 6),
+                                                           (unsigned)xor_here((int)bk_tr8, cb << 6), sb * 2 + hf, 0),
+                                      eb, dqa[hb][cb]);
+          }
+        }
+        // ---- heads x slots: S, dP (lane = slot, registers = heads) -> P, E -> dVd^T += dO^T P, dKd^T += Q^T E
+        {
+          f32x16 s, dp;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
+#pragma unroll
+          for (int st = 0; st < Tl::kDSteps; ++st) {
+            const unsigned xk = (unsigned)xor_here((int)bk_row, st << 5), xq = (unsigned)xor_here((int)bq_row, st << 5);
+            s = mfma_bf16(FragAddr<D>::row_frag(xq, hb, 0), FragAddr<D>::row_frag(xk, sb, 0), s);
+            dp = mfma_bf16(FragAddr<D>::row_frag(xq, hb, kGOff), FragAddr<D>::row_frag(xk, sb, kGOff), dp);
+          }
+          const bool live = c0 + sb * 32 + l32 < L;  // this lane's slot is attended
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            float pv[8], evv[8];
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2) {
+              const int b4 = hf * 2 + b2;
+              const float* st4 = stat + (hb * 32 + b4 * 8 + hi * 4) * 2;
+              const f32x4 ld01 = *(const f32x4*)st4, ld23 = *(const f32x4*)(st4 + 4);
+              const float l4[4] = {ld01[0], ld01[2], ld23[0], ld23[2]};
+              const float d4[4] = {ld01[1], ld01[3], ld23[1], ld23[3]};
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const int i = b4 * 4 + r;
+                const float pe = live ? fast_exp2(s[i] * c2 - l4[r]) : 0.f;
+                pv[b2 * 4 + r] = pe;
+                evv[b2 * 4 + r] = pe * (dp[i] - d4[r]);
+              }
+            }
+            const bf16x8 pb = pack8(pv), eb = pack8(evv);
+#pragma unroll
+            for (int cb = 0; cb < Tl::kDBlocks; ++cb) {
+              const unsigned x0 = (unsigned)xor_here((int)bq_tr, cb << 6), x8 = (unsigned)xor_here((int)bq_tr8, cb << 6);
+              dva[cb] = mfma_bf16(FragAddr<D>::tr_frag(x0, x8, hb * 2 + hf, kGOff), pb, dva[cb]);
+              dka[cb] = mfma_bf16(FragAddr<D>::tr_frag(x0, x8, hb * 2 + hf, 0), eb, dka[cb]);
+            }
+          }
+        }
+      }
+      // ---- store the block's dVdepth, dKdepth rows: lane = slot, 4 consecutive channels (8 bytes) at a time
+      const int slot = c0 + sb * 32 + l32;
+      if (slot < L) {
+        const float f = p.scale;
+#pragma unroll
+        for (int cb = 0; cb < Tl::kDBlocks; ++cb)
+#pragma unroll
+          for (int bq = 0; bq < 4; ++bq) {
+            const size_t off = (size_t)slot * RB + (cb * 32 + bq * 8 + hi * 4) * 2;
+            *(u32x2*)(dvd + off) = (u32x2){pack_bf16(dva[cb][4 * bq], dva[cb][4 * bq + 1]),
+                                           pack_bf16(dva[cb][4 * bq + 2], dva[cb][4 * bq + 3])};
+            *(u32x2*)(dkd + off) = (u32x2){pack_bf16(dka[cb][4 * bq] * f, dka[cb][4 * bq + 1] * f),
+                                           pack_bf16(dka[cb][4 * bq + 2] * f, dka[cb][4 * bq + 3] * f)};
+          }
+      }
     }
   }
-  for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
-    if (NOUT == 2) *(uint32_t*)(outp + (size_t)i * RB) = 0u;
-    else *(u32x2*)(outp + (size_t)i * RB) = (u32x2){0u, 0u};
+  // allocated but unattended slots get zero gradients
+  for (int i = L * (RB / 16) + lane; i < La * (RB / 16); i += 64) {
+    *(u32x4*)(dvd + (size_t)i * 16) = (u32x4){0u, 0u, 0u, 0u};
+    *(u32x4*)(dkd + (size_t)i * 16) = (u32x4){0u, 0u, 0u, 0u};
   }
+  // the heads' depth share of dQ: lane = head, 4 consecutive channels (16 bytes of fp32) at a time
 #pragma unroll
-  for (int s = 0; s < NS; ++s)
-    if (s * HS + hs < G) {
-      float* dst = p.dq_depth + head_row(s) * D + l16 * 8;
-      *(f32x4*)dst = (f32x4){dq[s][0], dq[s][1], dq[s][2], dq[s][3]};
-      *(f32x4*)(dst + 4) = (f32x4){dq[s][4], dq[s][5], dq[s][6], dq[s][7]};
+  for (int hb = 0; hb < NG; ++hb) {
+    const int h = hb * 32 + l32;
+    if (h < G) {
+      float* dst = p.dq_depth + ((size_t)(bh0 + h) * T + t) * D;
+#pragma unroll
+      for (int cb = 0; cb < Tl::kDBlocks; ++cb)
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq)
+          *(f32x4*)(dst + cb * 32 + bq * 8 + hi * 4) =
+              (f32x4){dqa[hb][cb][4 * bq], dqa[hb][cb][4 * bq + 1], dqa[hb][cb][4 * bq + 2], dqa[hb][cb][4 * bq + 3]};
     }
+  }
 }
 
 // ---------------------------------------------------------------- launchers
@@ -934,26 +987,25 @@ static hipError_t launch_bwd_bf16_d(BwdParams p, hipStream_t stream) {
   const long long g_dq = (long long)p.B * p.Hq * ((p.T + kDqWaves * 32 - 1) / (kDqWaves * 32));
   const long long kv_rows = (long long)p.B * p.Hk * p.T;
   const long long g_depth = (kv_rows * (D / 8) + 255) / 256;  // G <= 8: 256 / (d/8) positions per workgroup
-  const long long g_wide = (kv_rows + 3) / 4;                  // G > 8: one wave per position
+  const long long g_wide = kv_rows;                            // G > 8: one workgroup (of one wave) per position
   // every grid is checked before the first kernel is enqueued
   if (!grid_ok(g_delta) || !grid_ok(g_dkdv) || !grid_ok(g_dq) || !grid_ok(g_depth) || !grid_ok(g_wide))
     return kGridTooLarge;
   if (G > bwd_bf16_max_group()) return hipErrorInvalidValue;
+  // the group kernel gathers the G heads' rows of a position with 32-bit offsets from the first head
+  if (G > 8 && p.depth_alloc > 0 && (unsigned long long)G * p.T * (D * 2) >= 0xffffff00ull) return kGridTooLarge;
   p.dq_depth = (float*)((char*)p.rowstat + rowstat_bytes(p));
   hipError_t e = launch_kernel(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), stream, p.dO, p.O, p.LSE,
                                p.rowstat, rows);
   if (e != hipSuccess) return e;
   if (G > 1 && p.depth_alloc > 0) {
     const dim3 gd((unsigned)g_depth), gw((unsigned)g_wide), blk(256);
-    constexpr int HS = 64 / (D / 8);  // heads side by side in the wide kernel
-    const int ns = (G + HS - 1) / HS;
     if (G <= 2) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 2>, gd, blk, stream, p);
     else if (G <= 4) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 4>, gd, blk, stream, p);
     else if (G <= 8) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 8>, gd, blk, stream, p);
-    else if (ns <= 2) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 2, true>, gw, blk, stream, p);
-    else if (ns <= 4) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 4, true>, gw, blk, stream, p);
-    else if (ns <= 8) e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 8, true>, gw, blk, stream, p);
-    else e = launch_kernel(moda_bwd_depth_gqa_wide_kernel<D, 16, false>, gw, blk, stream, p);
+    // larger groups: one wave per position, the group's products on the matrix pipe
+    else if (G <= 32) e = launch_kernel(moda_bwd_depth_group_kernel<D, 1>, gw, dim3(64), stream, p);
+    else e = launch_kernel(moda_bwd_depth_group_kernel<D, 2>, gw, dim3(64), stream, p);
     if (e != hipSuccess) return e;
   }
   e = launch_kernel(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), stream, p);
