@@ -408,7 +408,8 @@ def main():
     common = {"traffic": measured_traffic(args.workload, "fwd"),
               "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
                                 "command), not measured by this run",
-              "kernel": ("moda_fwd_bf16_kernel<%d, 8>" % d) if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
+              "kernel": ("moda_fwd_bf16_kernel<%d, %d>" % (d, 4 if B * Hq * ((T + 255) // 256) < 256 else 8))
+              if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
               "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
               "flops_per_launch": flops, "bytes_per_launch": alg_bytes}
     if alg_bytes / 8.0e12 > flops / (PEAK_TFLOPS[dtype] * 1e12):
