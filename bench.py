@@ -405,9 +405,11 @@ def main():
     # Which roof bounds this workload: the time its algorithmic FLOPs need at the matrix (or, for
     # fp32, vector) peak against the time its algorithmic bytes need at the HBM peak.
     alg_bytes = esz * (B * T * d * (2 * Hq + 2 * Hk) + 2.0 * B * Hk * T * L * d) + 4.0 * B * Hq * T
-    common = {"traffic": measured_traffic(args.workload, "fwd"),
-              "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
-                                "command), not measured by this run",
+    stored = measured_traffic(args.workload, "fwd")
+    common = {"traffic": stored,
+              "traffic_source": ("stored: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                 "command), not measured by this run") if stored is not None
+              else "no counter run stored for this workload",
               "kernel": ("moda_fwd_bf16_kernel<%d, %d>" % (d, 4 if B * Hq * ((T + 255) // 256) < 256 else 8))
               if dtype == "bf16" else ("moda_fwd_f32_kernel<%d>" % d),
               "kernel_ms_mean": round(ms_kernel, 4), "kernel_ms_min": round(ms_min, 4),
