@@ -65,11 +65,6 @@ struct BwdCfg {
   static constexpr int kLds = (kRing > kXBytes ? kRing : kXBytes) + kAux;
 };
 
-__device__ __forceinline__ bf16x8 pack8(const float (&x)[8]) {
-  u32x4 t = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])};
-  return __builtin_bit_cast(bf16x8, t);
-}
-
 // ---------------------------------------------------------------- depth-slot gradients (G = 1)
 // The depth slots of 32 consecutive positions (row0 ...) of one head, handled by one wave in a
 // row-major mapping (d/8 lanes x 8 channels per row, 64 / (d/8) rows per wave step): dKdepth,

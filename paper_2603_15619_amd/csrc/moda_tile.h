@@ -160,6 +160,12 @@ struct TileLoader {
   }
 };
 
+// Eight fp32 -> one MFMA operand of packed bf16 (round to nearest even).
+__device__ __forceinline__ bf16x8 pack8(const float (&x)[8]) {
+  u32x4 t = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])};
+  return __builtin_bit_cast(bf16x8, t);
+}
+
 __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

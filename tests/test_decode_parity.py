@@ -48,7 +48,11 @@ def check(B, Hq, Hk, T, d, L, seed, kv_alloc=None, depth_alloc=None, scale=None)
 
 @pytest.mark.parametrize("B,Hq,Hk,T,d,L", [(2, 4, 4, 1000, 128, 15), (1, 8, 1, 777, 64, 5), (3, 6, 2, 300, 128, 0),
                                            (1, 16, 16, 5000, 128, 31), (2, 32, 2, 257, 64, 70), (1, 2, 2, 1, 128, 3),
-                                           (1, 2, 1, 17, 64, 0), (4, 16, 8, 4096, 128, 15)])
+                                           (1, 2, 1, 17, 64, 0), (4, 16, 8, 4096, 128, 15),
+                                           # more than 4 heads per group: the matrix-pipe kernel (5 heads; 40 heads =
+                                           # two chunks; the paper's kernel geometry on a long ragged cache; no slots)
+                                           (1, 10, 2, 333, 128, 7), (1, 40, 1, 1500, 64, 33),
+                                           (1, 64, 8, 20011, 64, 64), (2, 16, 2, 2049, 128, 0)])
 def test_decode_shapes(B, Hq, Hk, T, d, L):
     check(B, Hq, Hk, T, d, L, 900 + T + L)
 
@@ -56,6 +60,7 @@ def test_decode_shapes(B, Hq, Hk, T, d, L):
 def test_decode_cache_strides_and_scale():
     check(2, 4, 2, 500, 128, 3, 31, kv_alloc=1024, depth_alloc=8)
     check(1, 8, 8, 129, 64, 2, 32, kv_alloc=130, scale=0.3)
+    check(1, 8, 1, 500, 64, 3, 36, kv_alloc=600, depth_alloc=8, scale=0.2)
 
 
 def test_decode_long_cache():
