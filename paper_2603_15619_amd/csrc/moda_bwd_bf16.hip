@@ -545,29 +545,37 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
     ld.issue(v_buf, kt * 64, smem_addr + stage * C::kStageBytes + Tl::kBytes);
   };
 
-  issue(0, 0);
-  for (int kt = 0; kt < nt; ++kt) {
-    const int stage = kt & 1;
-    wait_copies();
-    __syncthreads();
-    if (kt + 1 < nt) issue(kt + 1, stage ^ 1);
-    if (kt > wave_last) continue;
+  // One key tile: S^T, dP^T, dS^T and dQ^T += K^T dS^T for this wave's 32 queries.
+  auto tile = [&](int kt, int stage) {
     // per-lane fragment bases inside this stage (K tile; the V tile sits Tl::kBytes after it)
     const unsigned ktile = smem_addr + stage * C::kStageBytes;
     const unsigned b_row = fa.row + ktile, b_tr = fa.tr + ktile, b_tr8 = fa.tr8 + ktile;
 
     f32x16 s[2], dp[2];  // S^T, dP^T: [key block]; a lane holds 16 keys of its query
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = dp[kb][i] = 0.f;
+    // four independent accumulation chains per channel step
 #pragma unroll
-      for (int st = 0; st < Tl::kDSteps; ++st) {
-        const unsigned x = (unsigned)xor_here((int)b_row, st << 5);
+    for (int st = 0; st < Tl::kDSteps; ++st) {
+      const unsigned x = (unsigned)xor_here((int)b_row, st << 5);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
         s[kb] = mfma_bf16(fa.row_frag(x, kb, 0), qf[st], s[kb]);
         dp[kb] = mfma_bf16(fa.row_frag(x, kb, Tl::kBytes), dof[st], dp[kb]);
       }
     }
+    // Order for the scheduler: the LDS reads run one channel step (four fragments) ahead of the
+    // matrix instructions that consume them.
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int st = 0; st < Tl::kDSteps - 1; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_barrier(0);
 
     bf16x8 dsb[2][2];
     const int k0 = kt * 64;
@@ -593,13 +601,43 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
         dsb[kb][hf] = pack8(a);
       }
     }
-    // dQ^T += K^T dS^T  (contraction over the tile's 64 keys)
+    __builtin_amdgcn_sched_barrier(0);
+    // dQ^T += K^T dS^T  (contraction over the tile's 64 keys); transposed fragments two
+    // matrix instructions ahead
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int db = 0; db < Tl::kDBlocks; ++db)
         dq[db] = mfma_bf16(fa.tr_frag((unsigned)xor_here((int)b_tr, db << 6), (unsigned)xor_here((int)b_tr8, db << 6), ks, 0),
                            dsb[ks >> 1][ks & 1], dq[db]);
+    constexpr int NM = 4 * Tl::kDBlocks;
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int m = 0; m < NM - 2; ++m) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Every wave takes part in the copies and barriers of all nt tiles, but computes only on the
+  // tiles its queries see: first those (no branch around the products inside the loop, which
+  // made the compiler copy the accumulators from one register block to another every tile),
+  // then the rest.
+  issue(0, 0);
+  int kt = 0;
+  for (; kt <= wave_last; ++kt) {
+    const int stage = kt & 1;
+    wait_copies();
+    __syncthreads();
+    if (kt + 1 < nt) issue(kt + 1, stage ^ 1);
+    tile(kt, stage);
+  }
+  for (; kt < nt; ++kt) {
+    wait_copies();
+    __syncthreads();
+    if (kt + 1 < nt) issue(kt + 1, (kt & 1) ^ 1);
   }
   __syncthreads();
 
