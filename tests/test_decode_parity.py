@@ -57,6 +57,22 @@ def test_decode_shapes(B, Hq, Hk, T, d, L):
     check(B, Hq, Hk, T, d, L, 900 + T + L)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_decode_random_shapes(seed):
+    """Seeded random shapes: group sizes on both sides of the switch between the two partial
+    kernels, ragged cache lengths, cache and slot strides larger than what is attended."""
+    rng = np.random.default_rng(4200 + seed)
+    d = int(rng.choice([64, 128]))
+    Hk = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 33]))
+    B = int(rng.integers(1, 4))
+    T = int(rng.integers(1, 3000))
+    L = int(rng.choice([0, 1, 5, 31, 32, 33, 100]))
+    kv_alloc = T + int(rng.integers(0, 70))
+    depth_alloc = L + int(rng.integers(0, 5))
+    check(B, G * Hk, Hk, T, d, L, 4300 + seed, kv_alloc=kv_alloc, depth_alloc=depth_alloc)
+
+
 def test_decode_cache_strides_and_scale():
     check(2, 4, 2, 500, 128, 3, 31, kv_alloc=1024, depth_alloc=8)
     check(1, 8, 8, 129, 64, 2, 32, kv_alloc=130, scale=0.3)
