@@ -297,10 +297,129 @@ __device__ __forceinline__ void depth_grad_rows(const BwdParams& p, int bh, int 
   }
 }
 
+// ---------------------------------------------------------------- depth-slot gradients, grouped queries (2 <= G <= 8)
+// One row = one (batch, key/value head, position); d/8 lanes x 8 channels per row, `row` is
+// (b * Hk + g) * T + t of this thread's row (rows that do not exist: `live` false, they compute on
+// a clamped row and store nothing).  The GT (>= G) query heads of the group are resident (their Q
+// and dO rows, LSE, delta, and their depth share of dQ); the row's slots stream by, one prefetched
+// ahead.  Per slot i:
+//   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (summed in fp32, one
+//                                    rounding each),
+//   dQ_h     += e_{h,i} k_i          (left in the workspace, fp32, unscaled, for the dQ kernel).
+// Groups of up to 4 heads: runs inside the dK/dV kernel, for the 128 positions of a workgroup's
+// key tile, before or after its key-tile work: the phase is then bound by HBM (the slots read
+// once, their gradients written once), the key-tile work by the matrix pipe.
+template <int D, int GT>
+__device__ __forceinline__ void depth_gqa_row(const BwdParams& p, long long row, bool live, int l16) {
+  constexpr int LPR = D / 8, RB = D * 2;
+  const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
+  const long long rc = row;
+  const int t = (int)(rc % T);
+  const int bg = (int)(rc / T);
+  const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;
+  const float c2 = p.scale_log2;
+  u32x4 q[GT], g[GT];
+  float l2[GT], dl[GT], dq[GT][8];
+#pragma unroll
+  for (int j = 0; j < GT; ++j) {
+    const int bh = bh0 + min(j, G - 1);  // heads past the group repeat the last one with weight zero
+    q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
+    g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
+    const f32x2 st = *(const f32x2*)(p.rowstat + ((size_t)bh * T + t) * 2);
+    l2[j] = st[0];
+    dl[j] = st[1];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dq[j][k] = 0.f;
+  }
+  const size_t drow = (size_t)La * RB;
+  const char* kd = (const char*)p.Kdepth + (size_t)rc * drow + l16 * 16;
+  const char* vd = (const char*)p.Vdepth + (size_t)rc * drow + l16 * 16;
+  char* dkd = (char*)p.dKdepth + (size_t)rc * drow + l16 * 16;
+  char* dvd = (char*)p.dVdepth + (size_t)rc * drow + l16 * 16;
+
+  u32x4 kn = {0u, 0u, 0u, 0u}, vn = kn;
+  if (L > 0) {
+    kn = __builtin_nontemporal_load((const u32x4*)kd);
+    vn = __builtin_nontemporal_load((const u32x4*)vd);
+  }
+  for (int i = 0; i < L; ++i) {
+    const u32x4 kv = kn, vv = vn;
+    const int inext = min(i + 1, L - 1);
+    kn = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
+    vn = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
+    float kx[8], ak[8], av[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      kx[2 * k] = bf16_lo(kv[k]);
+      kx[2 * k + 1] = bf16_hi(kv[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) ak[k] = av[k] = 0.f;
+#pragma unroll
+    for (int j = 0; j < GT; ++j) {
+      float sdot = 0.f, gdot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        sdot = dot2_bf16(q[j][k], kv[k], sdot);
+        gdot = dot2_bf16(g[j][k], vv[k], gdot);
+      }
+      sdot = group_sum<LPR>(sdot);
+      gdot = group_sum<LPR>(gdot);
+      const float pe = j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
+      const float e = pe * (gdot - dl[j]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        av[2 * k] += pe * bf16_lo(g[j][k]);
+        av[2 * k + 1] += pe * bf16_hi(g[j][k]);
+        ak[2 * k] += e * bf16_lo(q[j][k]);
+        ak[2 * k + 1] += e * bf16_hi(q[j][k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dq[j][k] += e * kx[k];
+    }
+    if (live) {
+      const float f = p.scale;
+      const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
+      const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
+                        pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
+      __builtin_nontemporal_store(o1, (u32x4*)(dvd + (size_t)i * RB));
+      __builtin_nontemporal_store(o2, (u32x4*)(dkd + (size_t)i * RB));
+    }
+  }
+  if (live) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
+      *(u32x4*)(dvd + (size_t)i * RB) = z;
+      *(u32x4*)(dkd + (size_t)i * RB) = z;
+    }
+#pragma unroll
+    for (int j = 0; j < GT; ++j)
+      if (j < G) {
+        float* dst = p.dq_depth + ((size_t)(bh0 + j) * T + t) * D + l16 * 8;
+        *(f32x4*)dst = (f32x4){dq[j][0], dq[j][1], dq[j][2], dq[j][3]};
+        *(f32x4*)(dst + 4) = (f32x4){dq[j][4], dq[j][5], dq[j][6], dq[j][7]};
+      }
+  }
+}
+
+// The same rows as a kernel of its own: groups of 5 to 8 heads, where the arithmetic per fetched
+// byte (it grows with the group) makes the phase a vector-ALU job that the dK/dV kernel cannot
+// hide (measured at 8 heads: inside dK/dV it costs what it costs alone).
+template <int D, int GT>
+__global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p) {
+  constexpr int LPR = D / 8, ROWS = 256 / LPR;
+  const long long row = (long long)blockIdx.x * ROWS + threadIdx.x / LPR;  // (b * Hk + g) * T + t
+  const long long n_rows = (long long)p.B * p.Hk * p.T;
+  depth_gqa_row<D, GT>(p, row < n_rows ? row : n_rows - 1, row < n_rows, threadIdx.x % LPR);
+}
+
 // ---------------------------------------------------------------- dK, dV
 // Workgroup = 128 keys (4 waves x 32 keys).  Accumulators hold dK^T, dV^T
 // ([channel][key]: a lane owns one key and 64 of its channels).
-template <int D>
+// GT: 0 = one query head per key/value head, more than 4 heads per group, or no depth slots;
+// 2, 4 = the depth-slot gradients of a group of up to GT heads are taken here as well
+// (depth_gqa_row).
+template <int D, int GT>
 __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   using Tl = Tile<D>;
   using C = BwdCfg<D>;
@@ -331,6 +450,17 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
   const bool own_depth = G == 1 && p.depth_alloc > 0;
   const bool depth_first = ((blockIdx.x >> 3) & 1) != 0;
   if (own_depth && depth_first) depth_grad_rows<D>(p, bg, kw0, lane);
+  // grouped queries: the workgroup's 128 positions, 256 / (d/8) at a time
+  auto group_depth = [&]() {
+    if constexpr (GT > 0) {
+      constexpr int LPR = D / 8, ROWS = 256 / LPR;
+      for (int r0 = 0; r0 < 128; r0 += ROWS) {
+        const int t = j0 + r0 + tid / LPR;
+        depth_gqa_row<D, GT>(p, (long long)bg * T + min(t, T - 1), t < T, tid % LPR);
+      }
+    }
+  };
+  if (GT > 0 && depth_first) group_depth();
 
   // resident K and V fragments of this wave's 32 keys (MFMA B operands: N = key, K = channels)
   bf16x8 kf[Tl::kDSteps], vf[Tl::kDSteps];
@@ -499,6 +629,7 @@ __global__ __launch_bounds__(256, 2) void moda_bwd_dkdv_kernel(BwdParams p) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
   if (own_depth && !depth_first) depth_grad_rows<D>(p, bg, kw0, lane);
+  if (GT > 0 && !depth_first) group_depth();
 }
 
 // ---------------------------------------------------------------- dQ
@@ -710,111 +841,6 @@ __global__ __launch_bounds__(NW * 64, 2) void moda_bwd_dq_kernel(BwdParams p) {
         *(u32x4*)(dQb + (size_t)t * Tl::kRowBytes + l16 * 16) = ov;
       }
     }
-  }
-}
-
-// ---------------------------------------------------------------- depth-slot gradients, grouped queries
-// One row = one (batch, key/value head, position); d/8 lanes x 8 channels per row.  The GT
-// (>= G, G <= 8) query heads of the group are resident (their Q and dO rows, LSE, delta, and
-// their depth share of dQ); the row's slots stream by, one prefetched ahead.  Per slot i:
-//   dVdepth_i = sum_h p_{h,i} dO_h,  dKdepth_i = scale sum_h e_{h,i} q_h  (summed in fp32, one
-//                                    rounding each),
-//   dQ_h     += e_{h,i} k_i          (left in the workspace, fp32, unscaled, for the dQ kernel).
-template <int D, int GT>
-__global__ __launch_bounds__(256, 2) void moda_bwd_depth_gqa_kernel(BwdParams p) {
-  constexpr int LPR = D / 8, ROWS = 256 / LPR, RB = D * 2;
-  const int T = p.T, L = p.depth_count, La = p.depth_alloc, G = p.Hq / p.Hk;
-  const int tid = threadIdx.x, l16 = tid % LPR;
-  const long long row = (long long)blockIdx.x * ROWS + tid / LPR;  // (b * Hk + g) * T + t
-  const long long n_rows = (long long)p.B * p.Hk * T;
-  const bool live = row < n_rows;
-  const long long rc = live ? row : n_rows - 1;
-  const int t = (int)(rc % T);
-  const int bg = (int)(rc / T);
-  const int bh0 = (bg / p.Hk) * p.Hq + (bg % p.Hk) * G;
-  const float c2 = p.scale_log2;
-
-  u32x4 q[GT], g[GT];
-  float l2[GT], dl[GT], dq[GT][8];
-#pragma unroll
-  for (int j = 0; j < GT; ++j) {
-    const int bh = bh0 + min(j, G - 1);  // heads past the group repeat the last one with weight zero
-    q[j] = *(const u32x4*)((const char*)p.Q + ((size_t)bh * T + t) * RB + l16 * 16);
-    g[j] = *(const u32x4*)((const char*)p.dO + ((size_t)bh * T + t) * RB + l16 * 16);
-    const f32x2 st = *(const f32x2*)(p.rowstat + ((size_t)bh * T + t) * 2);
-    l2[j] = st[0];
-    dl[j] = st[1];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) dq[j][k] = 0.f;
-  }
-  const size_t drow = (size_t)La * RB;
-  const char* kd = (const char*)p.Kdepth + (size_t)rc * drow + l16 * 16;
-  const char* vd = (const char*)p.Vdepth + (size_t)rc * drow + l16 * 16;
-  char* dkd = (char*)p.dKdepth + (size_t)rc * drow + l16 * 16;
-  char* dvd = (char*)p.dVdepth + (size_t)rc * drow + l16 * 16;
-
-  u32x4 kn = {0u, 0u, 0u, 0u}, vn = kn;
-  if (L > 0) {
-    kn = __builtin_nontemporal_load((const u32x4*)kd);
-    vn = __builtin_nontemporal_load((const u32x4*)vd);
-  }
-  for (int i = 0; i < L; ++i) {
-    const u32x4 kv = kn, vv = vn;
-    const int inext = min(i + 1, L - 1);
-    kn = __builtin_nontemporal_load((const u32x4*)(kd + (size_t)inext * RB));
-    vn = __builtin_nontemporal_load((const u32x4*)(vd + (size_t)inext * RB));
-    float kx[8], ak[8], av[8];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      kx[2 * k] = bf16_lo(kv[k]);
-      kx[2 * k + 1] = bf16_hi(kv[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) ak[k] = av[k] = 0.f;
-#pragma unroll
-    for (int j = 0; j < GT; ++j) {
-      float sdot = 0.f, gdot = 0.f;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        sdot = dot2_bf16(q[j][k], kv[k], sdot);
-        gdot = dot2_bf16(g[j][k], vv[k], gdot);
-      }
-      sdot = group_sum<LPR>(sdot);
-      gdot = group_sum<LPR>(gdot);
-      const float pe = j < G ? fast_exp2(sdot * c2 - l2[j]) : 0.f;
-      const float e = pe * (gdot - dl[j]);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        av[2 * k] += pe * bf16_lo(g[j][k]);
-        av[2 * k + 1] += pe * bf16_hi(g[j][k]);
-        ak[2 * k] += e * bf16_lo(q[j][k]);
-        ak[2 * k + 1] += e * bf16_hi(q[j][k]);
-      }
-#pragma unroll
-      for (int k = 0; k < 8; ++k) dq[j][k] += e * kx[k];
-    }
-    if (live) {
-      const float f = p.scale;
-      const u32x4 o1 = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3]), pack_bf16(av[4], av[5]), pack_bf16(av[6], av[7])};
-      const u32x4 o2 = {pack_bf16(ak[0] * f, ak[1] * f), pack_bf16(ak[2] * f, ak[3] * f),
-                        pack_bf16(ak[4] * f, ak[5] * f), pack_bf16(ak[6] * f, ak[7] * f)};
-      __builtin_nontemporal_store(o1, (u32x4*)(dvd + (size_t)i * RB));
-      __builtin_nontemporal_store(o2, (u32x4*)(dkd + (size_t)i * RB));
-    }
-  }
-  if (live) {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int i = L; i < La; ++i) {  // allocated but unattended slots get zero gradients
-      *(u32x4*)(dvd + (size_t)i * RB) = z;
-      *(u32x4*)(dkd + (size_t)i * RB) = z;
-    }
-#pragma unroll
-    for (int j = 0; j < GT; ++j)
-      if (j < G) {
-        float* dst = p.dq_depth + ((size_t)(bh0 + j) * T + t) * D + l16 * 8;
-        *(f32x4*)dst = (f32x4){dq[j][0], dq[j][1], dq[j][2], dq[j][3]};
-        *(f32x4*)(dst + 4) = (f32x4){dq[j][4], dq[j][5], dq[j][6], dq[j][7]};
-      }
   }
 }
 
@@ -1051,7 +1077,7 @@ size_t bwd_bf16_workspace_bytes(const BwdParams& p, int d) {
 
 int bwd_bf16_max_group() { return 64; }
 
-int bwd_bf16_kernels(const BwdParams& p) { return 3 + ((p.Hq / p.Hk > 1 && p.depth_alloc > 0) ? 1 : 0); }
+int bwd_bf16_kernels(const BwdParams& p) { return 3 + ((p.Hq / p.Hk > 4 && p.depth_alloc > 0) ? 1 : 0); }
 
 template <int D>
 static hipError_t launch_bwd_bf16_d(BwdParams p, hipStream_t stream) {
@@ -1063,7 +1089,7 @@ static hipError_t launch_bwd_bf16_d(BwdParams p, hipStream_t stream) {
   constexpr int kDqWaves = 4;
   const long long g_dq = (long long)p.B * p.Hq * ((p.T + kDqWaves * 32 - 1) / (kDqWaves * 32));
   const long long kv_rows = (long long)p.B * p.Hk * p.T;
-  const long long g_depth = (kv_rows * (D / 8) + 255) / 256;  // G <= 8: 256 / (d/8) positions per workgroup
+  const long long g_depth = (kv_rows * (D / 8) + 255) / 256;  // 5 <= G <= 8: 256 / (d/8) positions per workgroup
   const long long g_wide = kv_rows;                            // G > 8: one workgroup (of one wave) per position
   // every grid is checked before the first kernel is enqueued
   if (!grid_ok(g_delta) || !grid_ok(g_dkdv) || !grid_ok(g_dq) || !grid_ok(g_depth) || !grid_ok(g_wide))
@@ -1075,17 +1101,24 @@ static hipError_t launch_bwd_bf16_d(BwdParams p, hipStream_t stream) {
   hipError_t e = launch_kernel(moda_bwd_delta_kernel<D>, dim3((unsigned)g_delta), dim3(256), stream, p.dO, p.O, p.LSE,
                                p.rowstat, rows);
   if (e != hipSuccess) return e;
-  if (G > 1 && p.depth_alloc > 0) {
-    const dim3 gd((unsigned)g_depth), gw((unsigned)g_wide), blk(256);
-    if (G <= 2) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 2>, gd, blk, stream, p);
-    else if (G <= 4) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 4>, gd, blk, stream, p);
-    else if (G <= 8) e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 8>, gd, blk, stream, p);
-    // larger groups: one wave per position, the group's products on the matrix pipe
-    else if (G <= 32) e = launch_kernel(moda_bwd_depth_group_kernel<D, 1>, gw, dim3(64), stream, p);
-    else e = launch_kernel(moda_bwd_depth_group_kernel<D, 2>, gw, dim3(64), stream, p);
+  if (G > 4 && p.depth_alloc > 0) {
+    if (G <= 8) {
+      e = launch_kernel(moda_bwd_depth_gqa_kernel<D, 8>, dim3((unsigned)g_depth), dim3(256), stream, p);
+    } else {
+      // large groups: one wave per position, the group's products on the matrix pipe
+      const dim3 gw((unsigned)g_wide);
+      if (G <= 32) e = launch_kernel(moda_bwd_depth_group_kernel<D, 1>, gw, dim3(64), stream, p);
+      else e = launch_kernel(moda_bwd_depth_group_kernel<D, 2>, gw, dim3(64), stream, p);
+    }
     if (e != hipSuccess) return e;
   }
-  e = launch_kernel(moda_bwd_dkdv_kernel<D>, dim3((unsigned)g_dkdv), dim3(256), stream, p);
+  {
+    const dim3 gk((unsigned)g_dkdv), blk(256);
+    const bool grouped = G > 1 && G <= 4 && p.depth_alloc > 0;  // the depth-slot gradients of the group run inside dK/dV
+    if (!grouped) e = launch_kernel(moda_bwd_dkdv_kernel<D, 0>, gk, blk, stream, p);
+    else if (G <= 2) e = launch_kernel(moda_bwd_dkdv_kernel<D, 2>, gk, blk, stream, p);
+    else e = launch_kernel(moda_bwd_dkdv_kernel<D, 4>, gk, blk, stream, p);
+  }
   if (e != hipSuccess) return e;
   return launch_kernel(moda_bwd_dq_kernel<D, kDqWaves>, dim3((unsigned)g_dq), dim3(kDqWaves * 64), stream, p);
 }

@@ -108,8 +108,9 @@ def test_new_entry_points_reject_bad_arguments_without_gpu(L):
     assert bwd(MODAShape(**dict(ok, Hq=256, Hk=2))) == 3   # more than 64 query heads per key/value head
     assert bwd(MODAShape(**dict(ok, dtype=0))) == 3
     assert bwd(MODAShape(**ok), ws_bytes=8) == 6
-    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 1) == 4               # grouped queries + depth slots
-    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 4  # 20 heads per group: still one depth kernel
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 1) == 3               # up to 4 heads per group: the depth-slot gradients run inside dK/dV
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=16))), 1) == 4  # 8 heads per group: a kernel of their own
+    assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=40))), 1) == 4  # 20 heads per group: likewise
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**dict(ok, Hq=2))), 1) == 3
     assert L.moda_kernels_per_call(ctypes.byref(MODAShape(**ok)), 0) == 1
 
