@@ -355,7 +355,7 @@ void moda_decode_partial_mfma_kernel(DecodeParams p) {
     // weights hold; any reference gives the same quotient).  The first block always raises it
     // (m = -inf; every block holds at least one key of the slice, so bm is finite, and the
     // factor exp2(-inf) = 0 scales the empty state).
-    const bool raise = bm > m + lazy;
+    const bool raise = bm > m + lazy || m == -INFINITY;
     if (__builtin_amdgcn_ballot_w64(raise) != 0) {  // (uniform)
       const float mn = raise ? bm : m;
       const float al = fast_exp2((m - mn) * c2);
