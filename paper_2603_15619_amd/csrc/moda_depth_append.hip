@@ -8,7 +8,7 @@
 
 namespace moda {
 
-constexpr int kAppendPerThread = 4;  // 16-byte chunks of K (and of V) per thread, all loaded before any store
+constexpr int kAppendPerThread = 2;  // 16-byte chunks of K (and of V) per thread, all loaded before any store
 
 __global__ __launch_bounds__(256) void moda_depth_append_kernel(const char* __restrict__ K, const char* __restrict__ V,
                                                                 char* __restrict__ Kd, char* __restrict__ Vd,
@@ -22,8 +22,11 @@ __global__ __launch_bounds__(256) void moda_depth_append_kernel(const char* __re
   for (int u = 0; u < kAppendPerThread; ++u) {
     const long long i = base + u * 256;
     if (i < n_chunks) {
-      kv[u] = __builtin_nontemporal_load((const u32x4*)(K + (size_t)i * 16));
-      vv[u] = __builtin_nontemporal_load((const u32x4*)(V + (size_t)i * 16));
+      // (ordinary loads: the layer's K / V have just been read by its attention and are served
+      //  from the caches where they still are; the stores are non-temporal, the cache is not
+      //  read again before the next layer)
+      kv[u] = *(const u32x4*)(K + (size_t)i * 16);
+      vv[u] = *(const u32x4*)(V + (size_t)i * 16);
     }
   }
 #pragma unroll
